@@ -1,0 +1,15 @@
+"""CPU ORACLE -- test infrastructure, not the product.
+
+A plain, slow, obviously-correct CPU evaluation of what one Sync EASGD round
+computes (paper Eq. (1), (2), (5), (6); Section 5.1 steps (1)-(5)).  It is the
+yardstick the HIP library is compared against and shares no code with it.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.
+
+* ``oracle.elastic``  -- exchange-and-update (C, double arithmetic, fp32 storage)
+* ``oracle.mlp_grad`` -- per-worker minibatch gradient of a dense ReLU MLP with
+  softmax cross-entropy (numpy, double arithmetic)
+"""
+from .elastic import (build, easgd_round, measgd_round, num_threads)  # noqa: F401
+from .mlp_grad import mlp_grad, mlp_grad_all_workers, layer_slices  # noqa: F401

@@ -1,0 +1,87 @@
+/*
+ * CPU ORACLE -- test infrastructure, not the product.
+ *
+ * Slow, plain evaluation of one Sync EASGD round's exchange-and-update,
+ * written from the paper's update rules:
+ *
+ *   worker, Eq. (1):   W^i_{t+1} = W^i_t - eta * ( dW^i_t + rho * (W^i_t - Wc_t) )
+ *   center, Eq. (2):   Wc_{t+1}  = Wc_t  + eta * sum_i rho * (W^i_t - Wc_t)
+ *   momentum worker, Eq. (5),(6):
+ *                      V^i_{t+1} = mu * V^i_t - eta * dW^i_t
+ *                      W^i_{t+1} = W^i_t + V^i_{t+1} - eta * rho * (W^i_t - Wc_t)
+ *   (the momentum variant keeps Eq. (2) for the center, Section 5.1 "Async MEASGD").
+ *
+ * The five steps of Sync EASGD (Section 5.1) collapse, on one memory, to:
+ * read Wc_t (the "broadcast"), sum the time-t differences over the workers
+ * (the "reduce"), apply Eq. (1) to every worker and Eq. (2) to the center.
+ * Both rules use the time-t values of W^i and Wc.
+ *
+ * State is stored as fp32 (the same bits the GPU library is given); every
+ * right-hand side is evaluated in double and rounded once when stored.
+ *
+ * Only tests/, the smoke check and the benchmark's cpu_baseline leg may call
+ * this file.  It shares no code with the HIP library.
+ *
+ * The elastic coefficient of the center is a separate argument so that the
+ * "conserved only when both coefficients match" property can be tested; the
+ * paper's Eq. (2) is center_coef = eta * rho.
+ */
+#include <stddef.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* W, G: [P][ld] (first N entries of each row are valid); Wc: [N]. In place on W, Wc. */
+void oracle_easgd_round(float *W, const float *G, float *Wc,
+                        int P, size_t N, size_t ld,
+                        double eta, double rho, double center_coef)
+{
+    long long j;
+#pragma omp parallel for schedule(static)
+    for (j = 0; j < (long long)N; ++j) {
+        const double c = (double)Wc[j];          /* Wc_t, seen by every worker */
+        double sum_diff = 0.0;                   /* sum_i (W^i_t - Wc_t) */
+        for (int i = 0; i < P; ++i) {
+            const double w = (double)W[(size_t)i * ld + j];
+            const double g = (double)G[(size_t)i * ld + j];
+            const double diff = w - c;
+            sum_diff += diff;
+            W[(size_t)i * ld + j] = (float)(w - eta * (g + rho * diff));     /* Eq. (1) */
+        }
+        Wc[j] = (float)(c + center_coef * sum_diff);                         /* Eq. (2) */
+    }
+}
+
+/* V: [P][ld] momentum buffers, in place. mu is the momentum rate. */
+void oracle_measgd_round(float *W, float *V, const float *G, float *Wc,
+                         int P, size_t N, size_t ld,
+                         double eta, double rho, double mu, double center_coef)
+{
+    long long j;
+#pragma omp parallel for schedule(static)
+    for (j = 0; j < (long long)N; ++j) {
+        const double c = (double)Wc[j];
+        double sum_diff = 0.0;
+        for (int i = 0; i < P; ++i) {
+            const size_t k = (size_t)i * ld + j;
+            const double w = (double)W[k];
+            const double g = (double)G[k];
+            const double diff = w - c;
+            sum_diff += diff;
+            /* Eq. (5); Eq. (6) uses V_{t+1} as it is stored, i.e. as an fp32 value */
+            const float v_new = (float)(mu * (double)V[k] - eta * g);
+            V[k] = v_new;
+            W[k] = (float)(w + (double)v_new - eta * rho * diff);            /* Eq. (6) */
+        }
+        Wc[j] = (float)(c + center_coef * sum_diff);                         /* Eq. (2) */
+    }
+}

@@ -1,0 +1,154 @@
+/*
+ * easgd.h -- C ABI of the MI355X (gfx950) Sync EASGD hot-path library.
+ *
+ * One Sync EASGD round (paper Section 5.1, steps (1)-(5)) for P worker
+ * replicas that all live in ONE GPU's memory:
+ *
+ *   step (1)      easgd_grad        every worker's minibatch gradient dW^i_t at W^i_t
+ *   steps (2)-(5) easgd_sync_round  broadcast of the center, reduction over the
+ *                                   workers, worker rule Eq. (1), center rule Eq. (2)
+ *                 measgd_round      the same with the momentum worker rule Eq. (5),(6)
+ *
+ * Conventions shared by every entry point
+ *   - every pointer marked DEVICE is a device (HBM) pointer owned by the caller;
+ *     the library never allocates, frees or keeps a pointer after the call returns;
+ *   - calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream); no host synchronisation happens inside;
+ *   - the return value is an easgd_status; on error nothing was launched and
+ *     easgd_last_error() describes the reason (thread-local string);
+ *   - buffers of one call must not overlap each other;
+ *   - all floating point is IEEE fp32 (storage and arithmetic);
+ *   - replica matrices are [P][ld] row-major: row i is worker i, its first N
+ *     entries are the parameters, entries [N, ld) are padding that is never
+ *     read or written.
+ *
+ * Packed parameter layout of a replica (the packed single-buffer idea of
+ * Section 5.2): for layer l = 0..L-1 in order, the weight matrix
+ * W_l[dims[l]][dims[l+1]] row-major followed by the bias b_l[dims[l+1]];
+ * N = sum_l (dims[l]*dims[l+1] + dims[l+1]).
+ */
+#ifndef EASGD_H
+#define EASGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EASGD_OK         =  0,
+    EASGD_EINVAL     = -1,   /* NULL pointer, P < 1, N == 0, ld < N, b < 1, bad dims, bad option */
+    EASGD_ELAUNCH    = -2,   /* the HIP runtime refused a launch (hipGetLastError text in last_error) */
+    EASGD_EWORKSPACE = -3,   /* workspace NULL, misaligned or smaller than easgd_grad_workspace_bytes */
+    EASGD_ERANGE     = -4    /* a size exceeds what the kernels index (see each call) */
+} easgd_status;
+
+/*
+ * Steps (2)-(5) of a Sync EASGD round, fused (Section 5.1; Eq. (1), Eq. (2)):
+ *
+ *   for every parameter j:   c = Wc[j]                                (the broadcast of Wc_t)
+ *     for every worker i:    d_i = W[i][j] - c                        (time-t values)
+ *                            W[i][j] <- W[i][j] - eta*(G[i][j] + rho*d_i)        Eq. (1)
+ *     Wc[j] <- c + eta*rho * (d_0 + d_1 + ... + d_{P-1})                         Eq. (2)
+ *
+ * The sum over the workers is taken in ascending i by one thread, so results
+ * are bitwise reproducible from run to run and independent of the launch shape.
+ *
+ *   W   DEVICE in/out [P][ld]   worker replicas W^i_t -> W^i_{t+1}
+ *   G   DEVICE in     [P][ld]   worker gradients dW^i_t (never written)
+ *   Wc  DEVICE in/out [N]       center weights Wc_t -> Wc_{t+1}
+ *   P >= 1, N >= 1, ld >= N (elements).
+ *
+ * Fast path: W, G, Wc 16-byte aligned and ld % 4 == 0 (128-bit accesses; N need
+ * not be a multiple of 4).  Otherwise a scalar kernel computes the same values.
+ * Errors: EASGD_EINVAL, EASGD_ELAUNCH.
+ */
+int easgd_sync_round(float *W, const float *G, float *Wc,
+                     int P, size_t N, size_t ld,
+                     float eta, float rho, void *stream);
+
+/*
+ * The same round with the momentum worker rule (Eq. (5), Eq. (6)); the center
+ * keeps Eq. (2).  delta is the momentum rate (the paper's mu).
+ *
+ *     V[i][j] <- delta*V[i][j] - eta*G[i][j]                                     Eq. (5)
+ *     W[i][j] <- W[i][j] + V[i][j](new) - eta*rho*d_i                            Eq. (6)
+ *
+ *   V   DEVICE in/out [P][ld]   momentum buffers V^i_t -> V^i_{t+1}
+ * Other arguments, alignment rule and errors as for easgd_sync_round.
+ */
+int measgd_round(float *W, float *V, const float *G, float *Wc,
+                 int P, size_t N, size_t ld,
+                 float eta, float rho, float delta, void *stream);
+
+/*
+ * Step (1) of the round (Section 5.1; forward/backward propagation of Section
+ * 2.2) for a dense ReLU multilayer perceptron with softmax cross-entropy loss,
+ * averaged over the b samples of each worker's minibatch.  Worker i uses its
+ * own weights W[i] and its own minibatch (X[i], y[i]); all P workers are
+ * processed by batched fp32 MFMA matrix products.
+ *
+ *   dims        HOST   in  [n_layers+1]  layer widths, e.g. {784,1024,1024,10};
+ *                                        hidden layers use ReLU, the last layer is linear
+ *   W           DEVICE in  [P][ld]       packed replicas (layout above)
+ *   X           DEVICE in  [P][b][dims[0]] row-major inputs
+ *   y           DEVICE in  [P][b]        int32 labels in [0, dims[n_layers])
+ *   G           DEVICE out [P][ld]       packed gradients; every one of the N valid
+ *                                        entries of every row is overwritten
+ *   loss        DEVICE out [P]           mean loss of each worker, or NULL
+ *   workspace   DEVICE     scratch of at least easgd_grad_workspace_bytes(...)
+ *                                        bytes, 256-byte aligned; contents undefined after
+ *
+ * Requirements: 1 <= n_layers <= 8, every dims[l] >= 1, dims[n_layers] <= 1024,
+ * P >= 1, b >= 1, ld >= N, W/G/X 16-byte aligned.  The ReLU derivative at exactly 0 is 0.
+ * Errors: EASGD_EINVAL, EASGD_EWORKSPACE, EASGD_ERANGE (an operand above 2^31-1
+ * elements per worker), EASGD_ELAUNCH.
+ */
+size_t easgd_grad_workspace_bytes(const int *dims, int n_layers, int P, int b);
+
+int easgd_grad(const int *dims, int n_layers,
+               const float *W, size_t ld,
+               const float *X, const int32_t *y, int P, int b,
+               float *G, float *loss,
+               void *workspace, size_t workspace_bytes, void *stream);
+
+/* Number of parameters N of the packed layout for `dims`; 0 on invalid input. */
+size_t easgd_mlp_num_params(const int *dims, int n_layers);
+
+/*
+ * Launch-shape knobs (performance only; results never depend on them).
+ * Returns EASGD_EINVAL for an unknown option or an out-of-range value.
+ */
+typedef enum {
+    EASGD_OPT_UPDATE_BLOCKS_PER_CU = 1,  /* 0 = one block per 1024-element tile (default); k>0 = persistent grid of k*CUs blocks */
+    EASGD_OPT_UPDATE_NONTEMPORAL   = 2,  /* 1 = streaming (non-temporal) loads/stores for W, G, V (default), 0 = plain */
+    EASGD_OPT_UPDATE_UNROLL        = 3   /* workers whose loads are issued together: 2, 4 (default) or 8 */
+} easgd_option;
+
+int easgd_set_option(int option, long value);
+long easgd_get_option(int option);
+
+/*
+ * Measurement aids (not part of the method): plain streaming kernels of known
+ * traffic, used to measure the attainable HBM bandwidth of the device and to
+ * calibrate hardware byte counters.  All pointers DEVICE, 16-byte aligned,
+ * n > 0 and n % 4 == 0 elements; asynchronous on `stream`.
+ *   easgd_stream_copy   dst[j] = src[j]            reads 4n bytes, writes 4n bytes
+ *   easgd_stream_triad  a[j] = b[j] + s*c[j]       reads 8n bytes, writes 4n bytes
+ * Errors: EASGD_EINVAL, EASGD_ELAUNCH.
+ */
+int easgd_stream_copy(float *dst, const float *src, size_t n, void *stream);
+int easgd_stream_triad(float *a, const float *b, const float *c, size_t n, float s, void *stream);
+
+/* Message for the last error returned on the calling thread ("" if none). */
+const char *easgd_last_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int easgd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EASGD_H */

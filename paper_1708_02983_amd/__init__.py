@@ -1,0 +1,20 @@
+"""MI355X-native Sync EASGD hot path (arXiv 1708.02983): Python face of the C-ABI HIP library.
+
+The binding (and with it the shared library) is loaded on first use, so that
+``python -m paper_1708_02983_amd.build`` can run before the library exists.
+"""
+import importlib
+
+_BINDING_NAMES = (
+    "EasgdError", "easgd_grad", "easgd_grad_workspace_bytes", "easgd_mlp_num_params", "easgd_sync_round",
+    "measgd_round", "stream_copy", "stream_triad", "get_option", "set_option", "lib", "version", "LIB_PATH",
+    "OPT_UPDATE_BLOCKS_PER_CU", "OPT_UPDATE_NONTEMPORAL", "OPT_UPDATE_UNROLL",
+)
+__all__ = list(_BINDING_NAMES)
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES or name == "binding":
+        mod = importlib.import_module(".binding", __name__)
+        return mod if name == "binding" else getattr(mod, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

@@ -1,0 +1,181 @@
+"""Thin ctypes binding of libeasgd_hip.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, checks their
+dtype / device / contiguity / size on the host, and passes raw device pointers
+and the current HIP stream through the C ABI declared in ``include/easgd.h``.
+All arithmetic of the round runs inside the library's kernels; there is no
+fallback: if the shared library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libeasgd_hip.so")
+
+EASGD_OK = 0
+OPT_UPDATE_BLOCKS_PER_CU = 1
+OPT_UPDATE_NONTEMPORAL = 2
+OPT_UPDATE_UNROLL = 3
+
+
+class EasgdError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"easgd error {code}: {message}")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} not found: build the HIP library first "
+            "(python -m paper_1708_02983_amd.build); there is no CPU fallback")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, f, i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_int
+    lib.easgd_sync_round.argtypes = [vp, vp, vp, i, sz, sz, f, f, vp]
+    lib.easgd_sync_round.restype = i
+    lib.measgd_round.argtypes = [vp, vp, vp, vp, i, sz, sz, f, f, f, vp]
+    lib.measgd_round.restype = i
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.easgd_grad_workspace_bytes.argtypes = [ip, i, i, i]
+    lib.easgd_grad_workspace_bytes.restype = sz
+    lib.easgd_grad.argtypes = [ip, i, vp, sz, vp, vp, i, i, vp, vp, vp, sz, vp]
+    lib.easgd_grad.restype = i
+    lib.easgd_mlp_num_params.argtypes = [ip, i]
+    lib.easgd_mlp_num_params.restype = sz
+    lib.easgd_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.easgd_stream_copy.restype = i
+    lib.easgd_stream_triad.argtypes = [vp, vp, vp, sz, f, vp]
+    lib.easgd_stream_triad.restype = i
+    lib.easgd_set_option.argtypes = [i, ctypes.c_long]
+    lib.easgd_set_option.restype = i
+    lib.easgd_get_option.argtypes = [i]
+    lib.easgd_get_option.restype = ctypes.c_long
+    lib.easgd_last_error.restype = ctypes.c_char_p
+    lib.easgd_version.restype = i
+    return lib
+
+
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library (for callers that want the raw entry points)."""
+    return _lib
+
+
+def _check(code: int) -> None:
+    if code != EASGD_OK:
+        raise EasgdError(code, _lib.easgd_last_error().decode())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(name: str, t: torch.Tensor, dtype, min_numel: int) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if t.numel() < min_numel:
+        raise ValueError(f"{name} holds {t.numel()} elements, needs {min_numel}")
+    return t.data_ptr()
+
+
+def _replica_shape(W: torch.Tensor, N: Optional[int]):
+    if W.dim() != 2:
+        raise ValueError("replica matrices must be [P][ld]")
+    P, ld = W.shape
+    return P, ld, (ld if N is None else int(N))
+
+
+def easgd_sync_round(W, G, Wc, eta: float, rho: float, N: Optional[int] = None, stream=None) -> None:
+    """Steps (2)-(5) of a Sync EASGD round, in place on W[P][ld] and Wc[N] (Eq. (1), Eq. (2))."""
+    P, ld, N = _replica_shape(W, N)
+    need = (P - 1) * ld + N
+    _check(_lib.easgd_sync_round(_dev("W", W, torch.float32, need), _dev("G", G, torch.float32, need),
+                                 _dev("Wc", Wc, torch.float32, N), P, N, ld, eta, rho, _stream(stream)))
+
+
+def measgd_round(W, V, G, Wc, eta: float, rho: float, delta: float, N: Optional[int] = None,
+                 stream=None) -> None:
+    """The same round with the momentum worker rule, in place on W, V and Wc (Eq. (5), (6), (2))."""
+    P, ld, N = _replica_shape(W, N)
+    need = (P - 1) * ld + N
+    _check(_lib.measgd_round(_dev("W", W, torch.float32, need), _dev("V", V, torch.float32, need),
+                             _dev("G", G, torch.float32, need), _dev("Wc", Wc, torch.float32, N),
+                             P, N, ld, eta, rho, delta, _stream(stream)))
+
+
+def _dims(dims: Sequence[int]):
+    arr = (ctypes.c_int * len(dims))(*[int(d) for d in dims])
+    return arr, len(dims) - 1
+
+
+def easgd_mlp_num_params(dims: Sequence[int]) -> int:
+    arr, L = _dims(dims)
+    return int(_lib.easgd_mlp_num_params(arr, L))
+
+
+def easgd_grad_workspace_bytes(dims: Sequence[int], P: int, b: int) -> int:
+    arr, L = _dims(dims)
+    return int(_lib.easgd_grad_workspace_bytes(arr, L, P, b))
+
+
+def easgd_grad(dims: Sequence[int], W, X, y, G, loss=None, workspace=None, stream=None):
+    """Step (1): gradients of all P workers into G[P][ld]; returns the workspace used."""
+    arr, L = _dims(dims)
+    if W.dim() != 2 or X.dim() != 3 or y.dim() != 2:
+        raise ValueError("expected W[P][ld], X[P][b][d_in], y[P][b]")
+    P, ld = W.shape
+    b = X.shape[1]
+    N = easgd_mlp_num_params(dims)
+    if N == 0:
+        raise ValueError(f"invalid layer widths {list(dims)}")
+    if X.shape[0] != P or X.shape[2] != dims[0] or tuple(y.shape) != (P, b):
+        raise ValueError("X / y shapes do not match W and dims")
+    need = (P - 1) * ld + N
+    nbytes = easgd_grad_workspace_bytes(dims, P, b)
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    _check(_lib.easgd_grad(arr, L, _dev("W", W, torch.float32, need), ld,
+                           _dev("X", X, torch.float32, P * b * dims[0]),
+                           _dev("y", y, torch.int32, P * b), P, b,
+                           _dev("G", G, torch.float32, need),
+                           None if loss is None else _dev("loss", loss, torch.float32, P),
+                           _dev("workspace", workspace, torch.uint8, nbytes), workspace.numel(),
+                           _stream(stream)))
+    return workspace
+
+
+def stream_copy(dst, src, stream=None) -> None:
+    """Measurement aid: dst[:] = src with the library's streaming copy kernel."""
+    n = src.numel()
+    _check(_lib.easgd_stream_copy(_dev("dst", dst, torch.float32, n), _dev("src", src, torch.float32, n), n, _stream(stream)))
+
+
+def stream_triad(a, b, c, s: float, stream=None) -> None:
+    """Measurement aid: a[:] = b + s*c (two reads, one write per element)."""
+    n = a.numel()
+    _check(_lib.easgd_stream_triad(_dev("a", a, torch.float32, n), _dev("b", b, torch.float32, n),
+                                   _dev("c", c, torch.float32, n), n, s, _stream(stream)))
+
+
+def set_option(option: int, value: int) -> None:
+    _check(_lib.easgd_set_option(option, value))
+
+
+def get_option(option: int) -> int:
+    return int(_lib.easgd_get_option(option))
+
+
+def version() -> int:
+    return int(_lib.easgd_version())

@@ -1,0 +1,173 @@
+// Fused elastic exchange-and-update of one Sync EASGD round
+// (Section 5.1 steps (2)-(5); worker rule Eq. (1) or Eq. (5),(6); center rule Eq. (2)).
+//
+// All P replicas and the center live in one HBM, so the paper's broadcast of
+// the center is one read of Wc[j] kept in registers and its tree reduction over
+// the workers is a register sum in ascending worker order.  Every operand is
+// read once and every result written once: this kernel is a pure HBM stream of
+// N*(12P+8) bytes (EASGD) or N*(20P+8) bytes (momentum).
+//
+// One thread owns a group of four consecutive parameters (one 128-bit access
+// per stream) for all workers.  Loads of UNROLL workers are issued back to back
+// before any arithmetic, so a thread keeps 2*UNROLL (3*UNROLL with momentum)
+// 16-byte loads in flight; a wave covers 1 KiB contiguous in each stream.
+#include "common.h"
+
+namespace easgd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT, typename T>
+__device__ __forceinline__ T stream_load(const T *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void stream_store(T *p, T v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// One worker's rule applied to T = float or f32x4 lanes.  Returns d = w - c.
+template <bool MOM, typename T>
+__device__ __forceinline__ T worker_rule(T &w, T &v, T g, T c, float eta, float rho, float alpha, float delta)
+{
+    const T d = w - c;
+    if constexpr (MOM) {
+        v = delta * v - eta * g;              // Eq. (5)
+        w = (w + v) - alpha * d;              // Eq. (6)
+    } else {
+        w = w - eta * (g + rho * d);          // Eq. (1)
+    }
+    return d;
+}
+
+// T-wide groups [0, n_groups) of every row; rows are `ld_groups` groups apart.
+template <bool MOM, bool NT, int UNROLL, typename T>
+__device__ __forceinline__ void elastic_group(T *__restrict__ W, T *__restrict__ V, const T *__restrict__ G,
+                                              T *__restrict__ Wc, int P, size_t j, size_t ld_groups,
+                                              float eta, float rho, float alpha, float delta)
+{
+    const T c = Wc[j];
+    T acc = c - c;                            // zero of type T
+    int i = 0;
+    for (; i + UNROLL <= P; i += UNROLL) {
+        T w[UNROLL], g[UNROLL], v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t k = (size_t)(i + u) * ld_groups + j;
+            w[u] = stream_load<NT>(W + k);
+            g[u] = stream_load<NT>(G + k);
+            if constexpr (MOM) v[u] = stream_load<NT>(V + k);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t k = (size_t)(i + u) * ld_groups + j;
+            acc += worker_rule<MOM>(w[u], v[u], g[u], c, eta, rho, alpha, delta);   // ascending i
+            stream_store<NT>(W + k, w[u]);
+            if constexpr (MOM) stream_store<NT>(V + k, v[u]);
+        }
+    }
+    for (; i < P; ++i) {
+        const size_t k = (size_t)i * ld_groups + j;
+        T w = stream_load<NT>(W + k), g = stream_load<NT>(G + k), v = w;
+        if constexpr (MOM) v = stream_load<NT>(V + k);
+        acc += worker_rule<MOM>(w, v, g, c, eta, rho, alpha, delta);
+        stream_store<NT>(W + k, w);
+        if constexpr (MOM) stream_store<NT>(V + k, v);
+    }
+    Wc[j] = c + alpha * acc;                  // Eq. (2)
+}
+
+// 128-bit path: n4 full groups of four parameters, then the N % 4 tail as scalars.
+template <bool MOM, bool NT, int UNROLL>
+__global__ __launch_bounds__(256) void elastic_vec4_kernel(float *__restrict__ W, float *__restrict__ V,
+                                                           const float *__restrict__ G, float *__restrict__ Wc,
+                                                           int P, size_t N, size_t ld,
+                                                           float eta, float rho, float alpha, float delta)
+{
+    const size_t n4 = N / 4;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < n4; j += stride)
+        elastic_group<MOM, NT, UNROLL, f32x4>((f32x4 *)W, (f32x4 *)V, (const f32x4 *)G, (f32x4 *)Wc,
+                                              P, j, ld / 4, eta, rho, alpha, delta);
+    const size_t tail = N - n4 * 4;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail)
+        elastic_group<MOM, false, 1, float>(W, V, G, Wc, P, n4 * 4 + threadIdx.x, ld, eta, rho, alpha, delta);
+}
+
+// Scalar path for operands that are not 16-byte aligned or ld % 4 != 0.
+template <bool MOM>
+__global__ __launch_bounds__(256) void elastic_scalar_kernel(float *__restrict__ W, float *__restrict__ V,
+                                                             const float *__restrict__ G, float *__restrict__ Wc,
+                                                             int P, size_t N, size_t ld,
+                                                             float eta, float rho, float alpha, float delta)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += stride)
+        elastic_group<MOM, false, 4, float>(W, V, G, Wc, P, j, ld, eta, rho, alpha, delta);
+}
+
+template <bool MOM, bool NT>
+static void launch_vec4(int unroll, dim3 grid, hipStream_t s, float *W, float *V, const float *G, float *Wc,
+                        int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
+{
+    switch (unroll) {
+    case 2: hipLaunchKernelGGL((elastic_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 8: hipLaunchKernelGGL((elastic_vec4_kernel<MOM, NT, 8>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    default: hipLaunchKernelGGL((elastic_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    }
+}
+
+template <bool MOM>
+static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, size_t N, size_t ld,
+                         float eta, float rho, float delta, void *stream)
+{
+    const char *name = MOM ? "measgd_round" : "easgd_sync_round";
+    if (!W || !G || !Wc || (MOM && !V)) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
+    if (P < 1) return fail(EASGD_EINVAL, "%s: P must be >= 1, got %d", name, P);
+    if (N == 0) return fail(EASGD_EINVAL, "%s: N must be >= 1", name);
+    if (ld < N) return fail(EASGD_EINVAL, "%s: ld (%zu) < N (%zu)", name, ld, N);
+    clear_error();
+
+    const Options &opt = options();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const float alpha = eta * rho;            // elastic coefficient of workers and center
+    const bool vec = aligned16(W) && aligned16(G) && aligned16(Wc) && (!MOM || aligned16(V)) && (ld % 4 == 0);
+    const size_t items = vec ? (N + 3) / 4 : N;        // threads wanted (tail rides on the last block)
+    size_t blocks = (items + 255) / 256;
+    if (opt.update_blocks_per_cu > 0) {
+        const size_t persistent = (size_t)opt.update_blocks_per_cu * (size_t)num_cus();
+        if (blocks > persistent) blocks = persistent;
+    }
+    if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loop covers the rest
+    const dim3 grid((unsigned)blocks);
+    if (vec) {
+        if (opt.update_nontemporal) launch_vec4<MOM, true>((int)opt.update_unroll, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        else launch_vec4<MOM, false>((int)opt.update_unroll, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    } else {
+        hipLaunchKernelGGL((elastic_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    }
+    return check_launch(name);
+}
+
+}  // namespace easgd
+
+extern "C" {
+
+int easgd_sync_round(float *W, const float *G, float *Wc, int P, size_t N, size_t ld,
+                     float eta, float rho, void *stream)
+{
+    return easgd::elastic_round<false>(W, nullptr, G, Wc, P, N, ld, eta, rho, 0.0f, stream);
+}
+
+int measgd_round(float *W, float *V, const float *G, float *Wc, int P, size_t N, size_t ld,
+                 float eta, float rho, float delta, void *stream)
+{
+    return easgd::elastic_round<true>(W, V, G, Wc, P, N, ld, eta, rho, delta, stream);
+}
+
+}  // extern "C"

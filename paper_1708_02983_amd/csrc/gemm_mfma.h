@@ -1,0 +1,222 @@
+// Batched fp32 GEMM on the CDNA matrix cores (v_mfma_f32_32x32x2_f32) for the
+// forward / backward passes of the per-worker dense models (Section 5.1 step (1),
+// Section 2.2).  One launch covers all P workers: every worker multiplies its
+// own operands, so the worker index is one more block coordinate.
+//
+//   C[w][m][n] = epilogue( sum_k A[w](m,k) * B[w](k,n) )
+//
+// Operand storage is described per operand:
+//   K_CONTIG   element (x,k) at ptr[x*ld + k]      (row-major M x K, or N x K)
+//   MN_CONTIG  element (x,k) at ptr[k*ld + x]      (row-major K x M, or K x N)
+// A may be augmented by a vector of ones at index a_ones along its contiguous
+// axis.  With the packed layout "weight matrix, then bias" this turns the bias
+// add of the forward pass and the bias gradient of the backward pass into one
+// more row of the same matrix product.
+//
+// Tiling: a block of WAVES_M x WAVES_N wavefronts owns a BM x BN tile of C; each
+// wavefront owns (BM/WAVES_M) x (BN/WAVES_N) of it as 32x32 MFMA accumulators.
+// K is walked in slabs of BK: the next slab travels global -> registers while the
+// current one is multiplied out of LDS, then registers -> the other LDS buffer.
+// LDS holds both operands k-major ([k][m] and [k][n], row pitch +4 floats) so an
+// MFMA operand fetch is one conflict-free ds_read_b32 per lane.
+#pragma once
+#include "common.h"
+
+namespace easgd {
+
+enum { K_CONTIG = 0, MN_CONTIG = 1 };
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct GemmArgs {
+    const float *A, *B, *mask;
+    float *C;
+    size_t a_ws, b_ws, c_ws, mask_ws;   // worker strides (elements)
+    size_t c_ss;                        // split stride of C (elements); split s writes C + s*c_ss
+    int lda, ldb, ldc, ldmask;
+    int M, N, K;
+    int a_lim;                          // number of stored elements of A along its contiguous axis
+    int a_ones;                         // index along that axis that reads as 1.0f, or -1
+    int k_per_split;                    // multiple of BK; splits = ceil(K / k_per_split)
+    int splits;
+    int tiles_m, tiles_n;
+    int P;
+};
+
+// Four elements idx0..idx0+3 along the contiguous axis of a row that starts at `row`.
+// Elements at or beyond `lim` read as 0, except index `ones` which reads as 1.
+template <bool VEC>
+__device__ __forceinline__ f32x4 fetch4(const float *row, int idx0, int lim, int ones, bool row_valid)
+{
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (!row_valid) return v;
+    if (VEC && idx0 + 3 < lim) return *reinterpret_cast<const f32x4 *>(row + idx0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int idx = idx0 + q;
+        if (idx < lim) v[q] = row[idx];
+        else if (idx == ones) v[q] = 1.0f;
+    }
+    return v;
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmArgs p)
+{
+    constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
+    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int PITCH_A = BM + 4, PITCH_B = BN + 4;
+    constexpr int CHUNKS_A = BM * BK / 4, CHUNKS_B = BN * BK / 4;
+    constexpr int IT_A = (CHUNKS_A + NTHREADS - 1) / NTHREADS, IT_B = (CHUNKS_B + NTHREADS - 1) / NTHREADS;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 4 == 0, "tile shape");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BK * PITCH_A];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK * PITCH_B];
+
+    // block -> (worker, split, tile_m, tile_n)
+    const int tiles = p.tiles_m * p.tiles_n;
+    int id = blockIdx.x;
+    const int tile = id % tiles; id /= tiles;
+    const int split = id % p.splits;
+    const int w = id / p.splits;
+    const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+    const int k_begin = split * p.k_per_split;
+    const int k_end = min(p.K, k_begin + p.k_per_split);
+
+    const float *__restrict__ A = p.A + (size_t)w * p.a_ws;
+    const float *__restrict__ B = p.B + (size_t)w * p.b_ws;
+    const int b_lim = (B_LAYOUT == MN_CONTIG) ? p.N : p.K;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / WAVES_N) * WTM, wn0 = (wave % WAVES_N) * WTN;
+
+    f32x4 ra[IT_A], rb[IT_B];
+
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < IT_A; ++it) {
+            const int c = tid + it * NTHREADS;
+            if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
+            if (A_LAYOUT == K_CONTIG) {
+                const int kq = c % (BK / 4), m = m0 + c / (BK / 4);
+                ra[it] = fetch4<VEC>(A + (size_t)m * p.lda, k0 + 4 * kq, min(p.a_lim, k_end), p.a_ones < k_end ? p.a_ones : -1, m < p.M);
+            } else {
+                const int mq = c % (BM / 4), k = k0 + c / (BM / 4);
+                ra[it] = fetch4<VEC>(A + (size_t)k * p.lda, m0 + 4 * mq, p.a_lim, p.a_ones, k < k_end);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT_B; ++it) {
+            const int c = tid + it * NTHREADS;
+            if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
+            if (B_LAYOUT == K_CONTIG) {
+                const int kq = c % (BK / 4), n = n0 + c / (BK / 4);
+                rb[it] = fetch4<VEC>(B + (size_t)n * p.ldb, k0 + 4 * kq, min(b_lim, k_end), -1, n < p.N);
+            } else {
+                const int nq = c % (BN / 4), k = k0 + c / (BN / 4);
+                rb[it] = fetch4<VEC>(B + (size_t)k * p.ldb, n0 + 4 * nq, b_lim, -1, k < k_end);
+            }
+        }
+    };
+
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < IT_A; ++it) {
+            const int c = tid + it * NTHREADS;
+            if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
+            if (A_LAYOUT == K_CONTIG) {
+                const int kq = c % (BK / 4), m = c / (BK / 4);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) As[buf][(4 * kq + q) * PITCH_A + m] = ra[it][q];
+            } else {
+                const int mq = c % (BM / 4), k = c / (BM / 4);
+                *reinterpret_cast<f32x4 *>(&As[buf][k * PITCH_A + 4 * mq]) = ra[it];
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT_B; ++it) {
+            const int c = tid + it * NTHREADS;
+            if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
+            if (B_LAYOUT == K_CONTIG) {
+                const int kq = c % (BK / 4), n = c / (BK / 4);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) Bs[buf][(4 * kq + q) * PITCH_B + n] = rb[it][q];
+            } else {
+                const int nq = c % (BN / 4), k = c / (BN / 4);
+                *reinterpret_cast<f32x4 *>(&Bs[buf][k * PITCH_B + 4 * nq]) = rb[it];
+            }
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int n_slabs = (k_end - k_begin + BK - 1) / BK;
+    if (n_slabs > 0) {
+        load_global(k_begin);
+        store_lds(0);
+    }
+    __syncthreads();
+
+    // MFMA operand fetch: lane l supplies A[m = l%32][k = l/32] and B[k = l/32][n = l%32]
+    const int frag_k = lane >> 5, frag_x = lane & 31;
+    for (int s = 0; s < n_slabs; ++s) {
+        const int buf = s & 1;
+        const bool more = (s + 1 < n_slabs);
+        if (more) load_global(k_begin + (s + 1) * BK);
+        const float *as = &As[buf][frag_k * PITCH_A + wm0 + frag_x];
+        const float *bs = &Bs[buf][frag_k * PITCH_B + wn0 + frag_x];
+        auto multiply = [&](int kk) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = as[kk * PITCH_A + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = bs[kk * PITCH_B + j * 32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        };
+        const int k_left = k_end - (k_begin + s * BK);
+        if (k_left >= BK) {
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 2) multiply(kk);
+        } else {
+            // short last slab: stop at the last k pair that holds data (the rest of the slab is zero)
+            for (int kk = 0; kk < k_left; kk += 2) multiply(kk);
+        }
+        if (more) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
+    float *__restrict__ C = p.C + (size_t)w * p.c_ws + (size_t)split * p.c_ss;
+    const float *__restrict__ mask = (EPI == EPI_MASK) ? p.mask + (size_t)w * p.mask_ws : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn0 + j * 32 + frag_x;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * frag_k + (r % 4);
+                if (m < p.M && n < p.N) {
+                    float v = acc[i][j][r];
+                    if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
+                    if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
+                    C[(size_t)m * p.ldc + n] = v;
+                }
+            }
+        }
+}
+
+}  // namespace easgd

@@ -1,0 +1,254 @@
+// Step (1) of a Sync EASGD round (Section 5.1): the minibatch gradient of every
+// worker at its own weights, for a dense ReLU MLP with softmax cross-entropy
+// (forward / backward propagation of Section 2.2), written straight into the
+// packed gradient buffer (the packed single-buffer layout of Section 5.2).
+//
+// Per layer l (d_in = dims[l], d_out = dims[l+1]) the packed block is the
+// (d_in+1) x d_out matrix [W_l ; b_l], so with a ones column appended to the
+// layer input A_l the three products are
+//   forward   Z_l      = [A_l 1] * [W_l ; b_l]                (b x d_out),  A_{l+1} = relu(Z_l)
+//   weights   [dW;db]  = [A_l 1]^T * dZ_l                     ((d_in+1) x d_out, contiguous in G)
+//   inputs    dZ_{l-1} = (dZ_l * W_l^T) masked by A_l > 0     (b x d_in)
+// The last layer's logits are produced as split-K partial sums that the softmax
+// kernel adds in ascending split order, so every sum has a fixed order.
+#include "gemm_mfma.h"
+
+namespace easgd {
+
+static constexpr int MAX_LAYERS = 8;
+static constexpr int MAX_CLASSES = 1024;
+static constexpr int MAX_SPLITS = 16;
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct GradPlan {
+    size_t N = 0;
+    size_t off[MAX_LAYERS] = {0};       // packed offset of layer l
+    size_t act_off[MAX_LAYERS] = {0};   // workspace offset (bytes) of A_l, l = 1..L-1
+    size_t logits_off = 0, dz_off[2] = {0, 0};
+    size_t bytes = 0;
+    int splits = 1, k_per_split = 0;
+};
+
+static constexpr int SPLIT_BK = 16;     // slab depth of the kernel that produces the logits
+
+static bool make_plan(const int *dims, int L, int P, int b, GradPlan &pl)
+{
+    if (!dims || L < 1 || L > MAX_LAYERS || P < 1 || b < 1) return false;
+    for (int l = 0; l <= L; ++l)
+        if (dims[l] < 1) return false;
+    size_t n = 0;
+    for (int l = 0; l < L; ++l) {
+        pl.off[l] = n;
+        n += (size_t)dims[l] * dims[l + 1] + dims[l + 1];
+    }
+    pl.N = n;
+    // split the long, skinny logits product over K so that enough blocks run
+    const int K = dims[L - 1] + 1;
+    int splits = (K + 127) / 128;
+    if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+    if (splits < 1) splits = 1;
+    int kps = (K + splits - 1) / splits;
+    kps = (kps + SPLIT_BK - 1) / SPLIT_BK * SPLIT_BK;
+    pl.k_per_split = kps;
+    pl.splits = (K + kps - 1) / kps;
+
+    size_t o = 0, widest = 0;
+    for (int l = 1; l < L; ++l) {
+        pl.act_off[l] = o;
+        o += align_up((size_t)P * b * dims[l] * sizeof(float), 256);
+    }
+    for (int l = 1; l <= L; ++l) widest = dims[l] > (int)widest ? dims[l] : widest;
+    pl.logits_off = o;
+    o += align_up((size_t)pl.splits * P * b * dims[L] * sizeof(float), 256);
+    for (int q = 0; q < 2; ++q) {
+        pl.dz_off[q] = o;
+        o += align_up((size_t)P * b * widest * sizeof(float), 256);
+    }
+    pl.bytes = o;
+    return true;
+}
+
+// Softmax cross-entropy on the logits of all workers.  One block per worker; each
+// of its wavefronts walks rows wave, wave+4, ... and handles one row at a time with
+// the classes spread over the lanes.  Sums use fixed shuffle trees and fixed orders.
+//   zpart [splits][P*b][C] partial logits;  dz [P*b][C] <- (softmax - onehot)/b;  loss[P] <- mean
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const float *__restrict__ zpart, const int *__restrict__ y,
+                                                           float *__restrict__ dz, float *__restrict__ loss,
+                                                           int b, int C, int splits, size_t split_stride)
+{
+    __shared__ float wave_loss[4];
+    const int w = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float inv_b = 1.0f / (float)b;
+    float my_loss = 0.f;
+    for (int r = wave; r < b; r += 4) {
+        const size_t row = (size_t)w * b + r;
+        const int label = y[row];
+        // up to MAX_CLASSES/64 = 16 classes per lane
+        float z[MAX_CLASSES / 64];
+        float zmax = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < MAX_CLASSES / 64; ++q) {
+            const int c = lane + 64 * q;
+            float v = -INFINITY;
+            if (c < C) {
+                v = 0.f;
+                for (int s = 0; s < splits; ++s) v += zpart[s * split_stride + row * C + c];
+            }
+            z[q] = v;
+            zmax = fmaxf(zmax, v);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o));
+        float sum = 0.f, zlabel = 0.f;      // zlabel: shifted logit of the true class (one lane holds it)
+#pragma unroll
+        for (int q = 0; q < MAX_CLASSES / 64; ++q) {
+            const int c = lane + 64 * q;
+            if (c < C) {
+                if (c == label) zlabel = z[q] - zmax;
+                z[q] = expf(z[q] - zmax);
+                sum += z[q];
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) zlabel += __shfl_xor(zlabel, o);
+        const float inv_sum = 1.0f / sum;
+#pragma unroll
+        for (int q = 0; q < MAX_CLASSES / 64; ++q) {
+            const int c = lane + 64 * q;
+            if (c < C) dz[row * C + c] = (z[q] * inv_sum - (c == label ? 1.f : 0.f)) * inv_b;
+        }
+        my_loss += logf(sum) - zlabel;      // -log softmax(label)
+    }
+    if (lane == 0) wave_loss[wave] = my_loss;
+    __syncthreads();
+    if (threadIdx.x == 0 && loss) loss[w] = (((wave_loss[0] + wave_loss[1]) + wave_loss[2]) + wave_loss[3]) * inv_b;
+}
+
+// ---- GEMM dispatch -------------------------------------------------------
+
+enum Kind { FWD, DW, DA };
+
+template <int BM, int BN, int BK, int WM, int WN, int AL, int BL, int EPI>
+static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
+{
+    GemmArgs a = a_in;
+    a.tiles_m = (a.M + BM - 1) / BM;
+    a.tiles_n = (a.N + BN - 1) / BN;
+    const dim3 grid((unsigned)((size_t)a.tiles_m * a.tiles_n * a.splits * a.P)), block(WM * WN * 64);
+    if (vec) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, true, EPI>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI>), grid, block, 0, s, a);
+}
+
+// Picks the tile shape: 128x128 when that still gives every CU about two blocks,
+// 64x64 otherwise; outputs at most 32 wide use a 128x32 tile.
+template <int AL, int BL, int EPI>
+static void launch_gemm(const GemmArgs &a, bool vec, hipStream_t s)
+{
+    if (a.N <= 32) {
+        launch_tile<128, 32, SPLIT_BK, 4, 1, AL, BL, EPI>(a, vec, s);
+        return;
+    }
+    const size_t big = (size_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.splits * a.P;
+    if (big >= (size_t)(2 * num_cus())) launch_tile<128, 128, 16, 2, 2, AL, BL, EPI>(a, vec, s);
+    else launch_tile<64, 64, 32, 2, 2, AL, BL, EPI>(a, vec, s);
+}
+
+static inline bool mult4(size_t x) { return (x & 3u) == 0; }
+
+}  // namespace easgd
+
+extern "C" {
+
+size_t easgd_mlp_num_params(const int *dims, int n_layers)
+{
+    easgd::GradPlan pl;
+    if (!easgd::make_plan(dims, n_layers, 1, 1, pl)) return 0;
+    return pl.N;
+}
+
+size_t easgd_grad_workspace_bytes(const int *dims, int n_layers, int P, int b)
+{
+    easgd::GradPlan pl;
+    if (!easgd::make_plan(dims, n_layers, P, b, pl)) return 0;
+    return pl.bytes;
+}
+
+int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const float *X, const int32_t *y,
+               int P, int b, float *G, float *loss, void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace easgd;
+    const int L = n_layers;
+    GradPlan pl;
+    if (!W || !X || !y || !G) return fail(EASGD_EINVAL, "easgd_grad: NULL pointer");
+    if (!make_plan(dims, L, P, b, pl))
+        return fail(EASGD_EINVAL, "easgd_grad: need 1 <= n_layers <= %d, all dims >= 1, P >= 1, b >= 1", MAX_LAYERS);
+    if (dims[L] > MAX_CLASSES) return fail(EASGD_EINVAL, "easgd_grad: at most %d classes, got %d", MAX_CLASSES, dims[L]);
+    if (ld < pl.N) return fail(EASGD_EINVAL, "easgd_grad: ld (%zu) < N (%zu)", ld, pl.N);
+    if (!aligned16(W) || !aligned16(G) || !aligned16(X)) return fail(EASGD_EINVAL, "easgd_grad: W, G, X must be 16-byte aligned");
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < pl.bytes)
+        return fail(EASGD_EWORKSPACE, "easgd_grad: workspace must be 256-byte aligned and hold %zu bytes (got %zu)", pl.bytes, workspace_bytes);
+    for (int l = 0; l < L; ++l) {
+        const size_t per_worker = (size_t)(dims[l] + 1) * dims[l + 1];
+        if (per_worker > 0x7fffffffull || (size_t)b * dims[l] > 0x7fffffffull || (size_t)b * dims[l + 1] > 0x7fffffffull)
+            return fail(EASGD_ERANGE, "easgd_grad: layer %d exceeds 2^31-1 elements per worker", l);
+    }
+    if ((size_t)P * b * (size_t)pl.splits > 0x7fffffffull) return fail(EASGD_ERANGE, "easgd_grad: P*b too large");
+    clear_error();
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    auto act = [&](int l) -> const float * { return l == 0 ? X : reinterpret_cast<const float *>(ws + pl.act_off[l]); };
+    float *logits = reinterpret_cast<float *>(ws + pl.logits_off);
+    float *dz[2] = {reinterpret_cast<float *>(ws + pl.dz_off[0]), reinterpret_cast<float *>(ws + pl.dz_off[1])};
+    const bool base_vec = mult4(ld);
+
+    // ---- forward propagation ----
+    for (int l = 0; l < L; ++l) {
+        const int d_in = dims[l], d_out = dims[l + 1];
+        const bool last = (l == L - 1);
+        GemmArgs a = {};
+        a.A = act(l); a.a_ws = (size_t)b * d_in; a.lda = d_in; a.a_lim = d_in; a.a_ones = d_in;
+        a.B = W + pl.off[l]; a.b_ws = ld; a.ldb = d_out;
+        a.C = last ? logits : const_cast<float *>(act(l + 1)); a.c_ws = (size_t)b * d_out; a.ldc = d_out;
+        a.M = b; a.N = d_out; a.K = d_in + 1; a.P = P;
+        a.splits = last ? pl.splits : 1;
+        a.k_per_split = last ? pl.k_per_split : ((a.K + 63) / 64 * 64);
+        a.c_ss = (size_t)P * b * d_out;
+        const bool vec = base_vec && mult4(d_in) && mult4(d_out) && mult4(pl.off[l]);
+        if (last) launch_gemm<K_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, s);
+        else launch_gemm<K_CONTIG, MN_CONTIG, EPI_RELU>(a, vec, s);
+    }
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3(P), dim3(256), 0, s, logits, y, dz[(L - 1) & 1], loss, b, dims[L],
+                       pl.splits, (size_t)P * b * dims[L]);
+
+    // ---- backward propagation ----
+    for (int l = L - 1; l >= 0; --l) {
+        const int d_in = dims[l], d_out = dims[l + 1];
+        const float *dz_l = dz[l & 1];
+        {   // [dW_l ; db_l] = [A_l 1]^T dZ_l, stored at the layer's place in the packed gradient
+            GemmArgs a = {};
+            a.A = act(l); a.a_ws = (size_t)b * d_in; a.lda = d_in; a.a_lim = d_in; a.a_ones = d_in;
+            a.B = dz_l; a.b_ws = (size_t)b * d_out; a.ldb = d_out;
+            a.C = G + pl.off[l]; a.c_ws = ld; a.ldc = d_out;
+            a.M = d_in + 1; a.N = d_out; a.K = b; a.P = P;
+            a.splits = 1; a.k_per_split = (a.K + 63) / 64 * 64;
+            launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(a, mult4(d_in) && mult4(d_out), s);
+        }
+        if (l > 0) {   // dZ_{l-1} = (dZ_l W_l^T) where A_l > 0
+            GemmArgs a = {};
+            a.A = dz_l; a.a_ws = (size_t)b * d_out; a.lda = d_out; a.a_lim = d_out; a.a_ones = -1;
+            a.B = W + pl.off[l]; a.b_ws = ld; a.ldb = d_out;
+            a.C = dz[(l - 1) & 1]; a.c_ws = (size_t)b * d_in; a.ldc = d_in;
+            a.mask = act(l); a.mask_ws = (size_t)b * d_in; a.ldmask = d_in;
+            a.M = b; a.N = d_in; a.K = d_out; a.P = P;
+            a.splits = 1; a.k_per_split = (a.K + 63) / 64 * 64;
+            launch_gemm<K_CONTIG, K_CONTIG, EPI_MASK>(a, base_vec && mult4(d_out) && mult4(pl.off[l]), s);
+        }
+    }
+    return check_launch("easgd_grad");
+}
+
+}  // extern "C"

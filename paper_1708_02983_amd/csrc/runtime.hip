@@ -1,0 +1,80 @@
+// Error string, options and device queries shared by the entry points.
+#include "common.h"
+#include <cstdio>
+#include <mutex>
+
+namespace easgd {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+int num_cus()
+{
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
+Options &options()
+{
+    static Options o;
+    return o;
+}
+
+}  // namespace easgd
+
+extern "C" {
+
+const char *easgd_last_error(void) { return easgd::g_err; }
+
+int easgd_version(void) { return 100; }
+
+int easgd_set_option(int option, long value)
+{
+    easgd::Options &o = easgd::options();
+    switch (option) {
+    case EASGD_OPT_UPDATE_BLOCKS_PER_CU:
+        if (value < 0 || value > 64) return easgd::fail(EASGD_EINVAL, "blocks per CU must be in [0,64], got %ld", value);
+        o.update_blocks_per_cu = value;
+        return EASGD_OK;
+    case EASGD_OPT_UPDATE_NONTEMPORAL:
+        if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "nontemporal must be 0 or 1, got %ld", value);
+        o.update_nontemporal = value;
+        return EASGD_OK;
+    case EASGD_OPT_UPDATE_UNROLL:
+        if (value != 2 && value != 4 && value != 8) return easgd::fail(EASGD_EINVAL, "unroll must be 2, 4 or 8, got %ld", value);
+        o.update_unroll = value;
+        return EASGD_OK;
+    default:
+        return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
+    }
+}
+
+long easgd_get_option(int option)
+{
+    const easgd::Options &o = easgd::options();
+    switch (option) {
+    case EASGD_OPT_UPDATE_BLOCKS_PER_CU: return o.update_blocks_per_cu;
+    case EASGD_OPT_UPDATE_NONTEMPORAL: return o.update_nontemporal;
+    case EASGD_OPT_UPDATE_UNROLL: return o.update_unroll;
+    default: return -1;
+    }
+}
+
+}  // extern "C"

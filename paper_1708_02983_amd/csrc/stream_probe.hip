@@ -1,0 +1,63 @@
+// Measurement aids: plain streaming kernels of known traffic.  They are used to
+// measure this GPU's attainable HBM bandwidth (the ceiling the elastic update is
+// compared with) and to calibrate hardware byte counters.  Not part of the method.
+#include "common.h"
+
+namespace easgd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// dst[j] = src[j]: n4 128-bit groups, 4n bytes read + 4n bytes written
+__global__ __launch_bounds__(256) void stream_copy_kernel(f32x4 *__restrict__ dst, const f32x4 *__restrict__ src, size_t n4)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < n4; j += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + j), dst + j);
+}
+
+// a[j] = b[j] + s*c[j]: two reads and one write per element, the mix of the EASGD update
+__global__ __launch_bounds__(256) void stream_triad_kernel(f32x4 *__restrict__ a, const f32x4 *__restrict__ b,
+                                                           const f32x4 *__restrict__ c, float s, size_t n4)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < n4; j += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(b + j) + s * __builtin_nontemporal_load(c + j), a + j);
+}
+
+static int probe_grid(size_t n4, dim3 &grid)
+{
+    size_t blocks = (n4 + 255) / 256;
+    if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;
+    grid = dim3((unsigned)blocks);
+    return 0;
+}
+
+}  // namespace easgd
+
+extern "C" {
+
+int easgd_stream_copy(float *dst, const float *src, size_t n, void *stream)
+{
+    using namespace easgd;
+    if (!dst || !src || n == 0 || (n & 3u) || !aligned16(dst) || !aligned16(src))
+        return fail(EASGD_EINVAL, "easgd_stream_copy: need non-NULL 16-byte aligned pointers and n %% 4 == 0, n > 0");
+    clear_error();
+    dim3 grid;
+    probe_grid(n / 4, grid);
+    hipLaunchKernelGGL(stream_copy_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)dst, (const f32x4 *)src, n / 4);
+    return check_launch("easgd_stream_copy");
+}
+
+int easgd_stream_triad(float *a, const float *b, const float *c, size_t n, float s, void *stream)
+{
+    using namespace easgd;
+    if (!a || !b || !c || n == 0 || (n & 3u) || !aligned16(a) || !aligned16(b) || !aligned16(c))
+        return fail(EASGD_EINVAL, "easgd_stream_triad: need non-NULL 16-byte aligned pointers and n %% 4 == 0, n > 0");
+    clear_error();
+    dim3 grid;
+    probe_grid(n / 4, grid);
+    hipLaunchKernelGGL(stream_triad_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)a, (const f32x4 *)b, (const f32x4 *)c, s, n / 4);
+    return check_launch("easgd_stream_triad");
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
+before touching the GPU (no kernel is launched in this file)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1708_02983_amd", "libeasgd_hip.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libeasgd_hip.so not built (run __graft_entry__.build())")
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "easgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:m?easgd)_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return ctypes.CDLL(LIB)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"easgd_sync_round", "measgd_round", "easgd_grad", "easgd_grad_workspace_bytes",
+            "easgd_mlp_num_params", "easgd_last_error", "easgd_version", "easgd_set_option",
+            "easgd_get_option", "easgd_stream_copy", "easgd_stream_triad"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/easgd.h but not exported"
+
+
+def test_num_params_and_workspace(lib):
+    lib.easgd_mlp_num_params.restype = ctypes.c_size_t
+    lib.easgd_grad_workspace_bytes.restype = ctypes.c_size_t
+    for dims, n in [((784, 10), 7850), ((784, 1024, 1024, 10), 1863690), ((3072, 2048, 2048, 10), 10510346)]:
+        arr = (ctypes.c_int * len(dims))(*dims)
+        assert lib.easgd_mlp_num_params(arr, len(dims) - 1) == n
+        ws = lib.easgd_grad_workspace_bytes(arr, len(dims) - 1, 4, 64)
+        assert ws > 0 and ws % 256 == 0
+    bad = (ctypes.c_int * 2)(784, 0)
+    assert lib.easgd_mlp_num_params(bad, 1) == 0
+    assert lib.easgd_grad_workspace_bytes(bad, 1, 4, 64) == 0
+
+
+def test_bad_arguments_are_rejected_without_a_launch(lib):
+    lib.easgd_last_error.restype = ctypes.c_char_p
+    f, sz, vp = ctypes.c_float, ctypes.c_size_t, ctypes.c_void_p
+    lib.easgd_sync_round.argtypes = [vp, vp, vp, ctypes.c_int, sz, sz, f, f, vp]
+    lib.measgd_round.argtypes = [vp, vp, vp, vp, ctypes.c_int, sz, sz, f, f, f, vp]
+    fake = 0x1000  # never dereferenced: every call below must fail validation first
+    assert lib.easgd_sync_round(None, fake, fake, 1, 4, 4, 0.1, 0.1, None) == -1
+    assert b"NULL" in lib.easgd_last_error()
+    assert lib.easgd_sync_round(fake, fake, fake, 0, 4, 4, 0.1, 0.1, None) == -1
+    assert lib.easgd_sync_round(fake, fake, fake, 1, 0, 4, 0.1, 0.1, None) == -1
+    assert lib.easgd_sync_round(fake, fake, fake, 1, 8, 4, 0.1, 0.1, None) == -1
+    assert b"ld" in lib.easgd_last_error()
+    assert lib.measgd_round(fake, None, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.easgd_grad.argtypes = [ip, ctypes.c_int, vp, sz, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
+    dims = (ctypes.c_int * 2)(784, 10)
+    assert lib.easgd_grad(dims, 1, None, 7850, fake, fake, 1, 1, fake, None, fake, 1 << 30, None) == -1
+    assert lib.easgd_grad(dims, 1, fake, 7000, fake, fake, 1, 1, fake, None, fake, 1 << 30, None) == -1   # ld < N
+    assert lib.easgd_grad(dims, 0, fake, 7850, fake, fake, 1, 1, fake, None, fake, 1 << 30, None) == -1
+    assert lib.easgd_grad(dims, 1, fake, 7850, fake, fake, 1, 1, fake, None, None, 0, None) == -3          # workspace
+    assert lib.easgd_grad(dims, 1, fake, 7850, fake, fake, 1, 1, fake, None, 0x1000, 16, None) == -3
+    many = (ctypes.c_int * 2)(784, 5000)
+    assert lib.easgd_grad(many, 1, fake, 784 * 5000 + 5000, fake, fake, 1, 1, fake, None, 0x1000, 1 << 30, None) == -1
+
+
+def test_options_roundtrip(lib):
+    lib.easgd_set_option.argtypes = [ctypes.c_int, ctypes.c_long]
+    lib.easgd_get_option.restype = ctypes.c_long
+    old = lib.easgd_get_option(3)
+    assert lib.easgd_set_option(3, 8) == 0 and lib.easgd_get_option(3) == 8
+    assert lib.easgd_set_option(3, 5) == -1
+    assert lib.easgd_set_option(99, 1) == -1
+    assert lib.easgd_set_option(3, old) == 0
+    assert lib.easgd_version() >= 100

@@ -1,0 +1,293 @@
+#!/usr/bin/env python3
+"""Benchmark of the Sync EASGD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1|cfg2|cfg3|cfg4|cfg5]
+
+A step is one whole Sync EASGD round over one batch of synthetic input that is
+already resident in HBM: `easgd_grad` for all P workers followed by the fused
+elastic update (`easgd_sync_round`, or `measgd_round` for momentum workloads);
+for the update-only workloads cfg4/cfg5 a step is the elastic update alone.
+The default workload is cfg2 (MLP 784-1024-1024-10, P=16, b=128); the default
+run also measures the elastic update at AlexNet size (cfg4, cfg5) and reports
+those under "elastic_update" in the same JSON line.
+
+Prints ONE JSON line.  Kernel-phase durations are measured with HIP events on
+the stream the kernels are launched on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+DESCRIPTIONS = {
+    "cfg1": "cfg1: softmax regression 784-10, P=4 workers, batch 64 each, Sync EASGD",
+    "cfg2": "cfg2: MLP 784-1024-1024-10 ReLU, P=16 workers, batch 128 each, Sync EASGD",
+    "cfg3": "cfg3: MLP 3072-2048-2048-10 ReLU, P=32 workers, batch 100 each, Sync MEASGD (momentum 0.9)",
+    "cfg4": "cfg4: elastic update only, P=8 replicas x 61M fp32 parameters, Sync EASGD",
+    "cfg5": "cfg5: elastic update only, P=16 replicas x 61M fp32 parameters, Sync MEASGD (momentum 0.9)",
+}
+
+
+def update_bytes(wl) -> int:
+    """Algorithmic HBM bytes of one elastic update: per worker element read W, G (and V), write W (and V);
+    per center element one read and one write."""
+    per_worker = 20 if wl.momentum else 12
+    return wl.N * (per_worker * wl.P + 8)
+
+
+def grad_flops(wl) -> int:
+    """Useful flops of one easgd_grad call: forward, weight-gradient and input-gradient products."""
+    total = 0
+    for l in range(len(wl.dims) - 1):
+        mnk = wl.batch * wl.dims[l] * wl.dims[l + 1]
+        total += 2 * mnk * (3 if l > 0 else 2)
+    return total * wl.P
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def _sum_ms(starts, stops):
+    return float(sum(a.elapsed_time(b) for a, b in zip(starts, stops)))
+
+
+# ---------------------------------------------------------------------------
+# GPU legs
+# ---------------------------------------------------------------------------
+
+def bench_training(hip, wl, steps, warmup):
+    import torch
+    ld = workloads.round_up(wl.N, 4)
+    w0 = workloads.init_packed_weights(wl)
+    dW = torch.from_numpy(workloads.replicate(w0, wl.P, ld)).cuda()
+    dWc = torch.from_numpy(w0.copy()).cuda()
+    dV = torch.zeros_like(dW) if wl.momentum else None
+    dG = torch.zeros_like(dW)
+    n_batches = min(wl.rounds, 16)
+    batches = []
+    for t in range(n_batches):
+        X, y = workloads.minibatch(wl, t)
+        batches.append((torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()))
+    ws = torch.empty(hip.easgd_grad_workspace_bytes(wl.dims, wl.P, wl.batch), dtype=torch.uint8, device="cuda")
+
+    def step(t, ev=None):
+        X, y = batches[t % n_batches]
+        if ev:
+            ev[0].record()
+        hip.easgd_grad(wl.dims, dW, X, y, dG, None, workspace=ws)
+        if ev:
+            ev[1].record()
+        if wl.momentum:
+            hip.measgd_round(dW, dV, dG, dWc, wl.eta, wl.rho, wl.delta, N=wl.N)
+        else:
+            hip.easgd_sync_round(dW, dG, dWc, wl.eta, wl.rho, N=wl.N)
+        if ev:
+            ev[2].record()
+
+    for t in range(warmup):
+        step(t)
+    e0, e1, e2 = _events(steps), _events(steps), _events(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        step(warmup + t, (e0[t], e1[t], e2[t]))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert bool(torch.isfinite(dWc).all()), "center weights diverged"
+    grad_ms = _sum_ms(e0, e1) / steps
+    upd_ms = _sum_ms(e1, e2) / steps
+    return {"elapsed_s": elapsed, "ms_per_step": 1e3 * elapsed / steps, "grad_ms": grad_ms, "update_ms": upd_ms}
+
+
+def bench_update_only(hip, wl, steps, warmup, pool=3):
+    import torch
+    P, N = wl.P, wl.N
+    dW = workloads.device_normal((P, N), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 1)
+    dWc = workloads.device_normal((N,), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 2)
+    dV = torch.zeros_like(dW) if wl.momentum else None
+    # gradients of consecutive rounds: a small pool of independent draws, cycled (footprint >> caches)
+    Gs = [workloads.device_normal((P, N), workloads.GRADIENT_STD, workloads.DEFAULT_SEED, 100 + t) for t in range(pool)]
+
+    def step(t):
+        if wl.momentum:
+            hip.measgd_round(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta)
+        else:
+            hip.easgd_sync_round(dW, Gs[t % pool], dWc, wl.eta, wl.rho)
+
+    for t in range(warmup):
+        step(t)
+    e0, e1 = _events(steps), _events(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        e0[t].record()
+        step(warmup + t)
+        e1[t].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert bool(torch.isfinite(dWc).all())
+    kernel_ms = _sum_ms(e0, e1) / steps
+    return {"elapsed_s": elapsed, "ms_per_step": 1e3 * elapsed / steps, "update_ms": kernel_ms}
+
+
+def triad_ceiling(hip, n=488_000_000, reps=20):
+    """Attainable HBM bandwidth of this device for a 2-read/1-write stream (GB/s)."""
+    import torch
+    a = torch.empty(n, dtype=torch.float32, device="cuda")
+    b = torch.ones_like(a)
+    c = torch.ones_like(a)
+    for _ in range(3):
+        hip.stream_triad(a, b, c, 0.5)
+    e0, e1 = _events(1)[0], _events(1)[0]
+    e0.record()
+    for _ in range(reps):
+        hip.stream_triad(a, b, c, 0.5)
+    e1.record()
+    torch.cuda.synchronize()
+    return 12.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def hbm_roofline(wl, update_ms, ceiling_gbs=None):
+    achieved = update_bytes(wl) / (update_ms * 1e-3) / 1e9
+    out = {"bound": "hbm", "kernel": "elastic_vec4_kernel (measgd)" if wl.momentum else "elastic_vec4_kernel (easgd)",
+           "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+           "algorithmic_bytes_per_launch": update_bytes(wl), "avg_launch_ms": round(update_ms, 4)}
+    if ceiling_gbs:
+        out["measured_triad_ceiling_GBs"] = round(ceiling_gbs, 1)
+        out["frac_of_triad_ceiling"] = round(achieved / ceiling_gbs, 4)
+    return out
+
+
+# ---------------------------------------------------------------------------
+# CPU baseline: the oracle, as it stands, on the host cores
+# ---------------------------------------------------------------------------
+
+def cpu_baseline(wl, budget_s=12.0):
+    import oracle
+    F = np.float32
+    cores = oracle.num_threads()
+    if wl.has_grad:
+        ld = workloads.round_up(wl.N, 4)
+        w0 = workloads.init_packed_weights(wl)
+        W = workloads.replicate(w0, wl.P, ld); Wc = w0.copy()
+        V = np.zeros_like(W)
+        X, y = workloads.minibatch(wl, 0)
+        done, t0 = 0, time.perf_counter()
+        while True:
+            G, _ = oracle.mlp_grad_all_workers(wl.dims, W, X, y)
+            if wl.momentum:
+                oracle.measgd_round(W, V, G, Wc, F(wl.eta), F(wl.rho), F(wl.delta), N=wl.N)
+            else:
+                oracle.easgd_round(W, G, Wc, F(wl.eta), F(wl.rho), N=wl.N)
+            done += 1
+            el = time.perf_counter() - t0
+            if el >= budget_s or done >= 200:
+                break
+        return {"value": round(done / el, 4), "unit": "rounds/s", "cores": cores, "kind": "oracle",
+                "sample": f"{done} whole rounds (numpy fp64 gradient of all {wl.P} workers + C elastic update) "
+                          f"of the same workload in {el:.1f} s"}
+    # update-only: a 1/8 slice of the parameter index (the update is independent per parameter)
+    frac = 8
+    n = wl.N // frac
+    W, Wc = workloads.update_state(wl.P, n)
+    G = workloads.update_gradients(wl.P, n, 0)
+    V = np.zeros_like(W)
+    done, t0 = 0, time.perf_counter()
+    while True:
+        if wl.momentum:
+            oracle.measgd_round(W, V, G, Wc, F(wl.eta), F(wl.rho), F(wl.delta))
+        else:
+            oracle.easgd_round(W, G, Wc, F(wl.eta), F(wl.rho))
+        done += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s / 2 or done >= 400:
+            break
+    return {"value": round(done / el / frac, 4), "unit": "rounds/s", "cores": cores, "kind": "oracle",
+            "sample": f"{done} rounds on a 1/{frac} slice of the parameter index ({n} of {wl.N} parameters, all "
+                      f"{wl.P} replicas) in {el:.1f} s; rate divided by {frac}",
+            "GBs": round(update_bytes(wl) / frac * done / el / 1e9, 2)}
+
+
+# ---------------------------------------------------------------------------
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(workloads.WORKLOADS))
+    ap.add_argument("--no-extras", action="store_true", help="skip the cfg4/cfg5 elastic-update legs of the default run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all P replicas live in one HBM); --gpus must be 1. "
+              "How the round would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1708_02983_amd as hip      # raises if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    wl = workloads.WORKLOADS[args.workload]
+    steps = args.steps if args.steps is not None else (300 if wl.has_grad else 100)
+    warmup = args.warmup if args.warmup is not None else (20 if wl.has_grad else 5)
+
+    ceiling = triad_ceiling(hip)
+    line = {"metric": "Sync EASGD rounds/sec", "unit": "rounds/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": DESCRIPTIONS[args.workload], "P": wl.P, "params_per_replica": wl.N,
+                       "eta": wl.eta, "rho": wl.rho, "delta": wl.delta}}
+    if wl.has_grad:
+        r = bench_training(hip, wl, steps, warmup)
+        tflops = grad_flops(wl) / (r["grad_ms"] * 1e-3) / 1e12
+        line.update({"value": round(steps / r["elapsed_s"], 2), "ms_per_step": round(r["ms_per_step"], 4),
+                     "phases_ms": {"easgd_grad": round(r["grad_ms"], 4), "elastic_update": round(r["update_ms"], 4)}})
+        line["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all products of easgd_grad)",
+                            "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
+                            "useful_flops_per_launch": grad_flops(wl), "avg_launch_ms": round(r["grad_ms"], 4)}
+        line["update_in_round"] = {"GBs_algorithmic": round(update_bytes(wl) / (r["update_ms"] * 1e-3) / 1e9, 1),
+                                   "note": "replicas of this workload fit the 256 MB last-level cache only partly; "
+                                           "not an HBM figure"}
+    else:
+        r = bench_update_only(hip, wl, steps, warmup)
+        line.update({"value": round(steps / r["elapsed_s"], 2), "ms_per_step": round(r["ms_per_step"], 4)})
+        line["roofline"] = hbm_roofline(wl, r["update_ms"], ceiling)
+
+    if wl.has_grad and not args.no_extras:
+        extra = {}
+        for name in ("cfg4", "cfg5"):
+            w2 = workloads.WORKLOADS[name]
+            r2 = bench_update_only(hip, w2, 100, 5)
+            extra[name] = {"workload": DESCRIPTIONS[name], "rounds_per_s": round(100 / r2["elapsed_s"], 2),
+                           "ms_per_step": round(r2["ms_per_step"], 4), "roofline": hbm_roofline(w2, r2["update_ms"], ceiling)}
+            torch.cuda.empty_cache()
+        line["elastic_update"] = extra
+
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl)
+        if "elastic_update" in line:
+            line["elastic_update"]["cfg4"]["cpu_baseline"] = cpu_baseline(workloads.WORKLOADS["cfg4"], budget_s=8.0)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

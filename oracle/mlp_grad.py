@@ -15,7 +15,7 @@ b_l[d_out]; layers back to back (the packed single buffer of Section 5.2).
 """
 from __future__ import annotations
 
-from typing import List, Sequence, Tuple
+from typing import Iterable, List, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -31,10 +31,20 @@ def layer_slices(dims: Sequence[int]) -> List[Tuple[slice, slice]]:
     return out
 
 
-def mlp_grad(dims: Sequence[int], w_packed: np.ndarray, X: np.ndarray, y: np.ndarray):
+def mlp_grad(dims: Sequence[int], w_packed: np.ndarray, X: np.ndarray, y: np.ndarray,
+             gate_flips: Iterable[Tuple[int, int, int]] = (), near_zero: Optional[list] = None,
+             near_zero_rel: float = 0.0):
     """Gradient (packed, fp32) and mean loss (float) for ONE worker.
 
-    w_packed: [>=N] fp32, X: [b][dims[0]] fp32, y: [b] integer labels in [0, dims[-1])."""
+    w_packed: [>=N] fp32, X: [b][dims[0]] fp32, y: [b] integer labels in [0, dims[-1]).
+
+    The ReLU derivative is a step: a hidden unit whose pre-activation z is within
+    rounding of zero has a gate (z > 0) that fp32 and fp64 arithmetic may decide
+    differently, and either decision is a valid gradient of the fp32 computation.
+    By default the gate is decided here in double.  For such ties a caller can
+    ask which units are near zero (``near_zero`` list is filled with
+    (layer, sample, unit) where |z| <= near_zero_rel * max|Z_layer|) and evaluate
+    the other decision by passing those triples in ``gate_flips``."""
     sl = layer_slices(dims)
     L = len(sl)
     b = X.shape[0]
@@ -55,6 +65,12 @@ def mlp_grad(dims: Sequence[int], w_packed: np.ndarray, X: np.ndarray, y: np.nda
     rows = np.arange(b)
     loss = float(-log_p[rows, y].mean())
 
+    flips = list(gate_flips)
+    if near_zero is not None:
+        for l in range(L - 1):
+            n_idx, u_idx = np.nonzero(np.abs(zs[l]) <= near_zero_rel * np.abs(zs[l]).max())
+            near_zero.extend((l, int(n), int(u)) for n, u in zip(n_idx, u_idx))
+
     # backward propagation
     dz = np.exp(log_p)
     dz[rows, y] -= 1.0
@@ -66,7 +82,11 @@ def mlp_grad(dims: Sequence[int], w_packed: np.ndarray, X: np.ndarray, y: np.nda
         grad[b_sl] = dz.sum(axis=0)
         if l > 0:
             da = dz @ Ws[l].T
-            dz = da * (zs[l - 1] > 0.0)     # ReLU derivative, 0 at z == 0
+            gate = zs[l - 1] > 0.0          # ReLU derivative, 0 at z == 0
+            for (fl, n, u) in flips:
+                if fl == l - 1:
+                    gate[n, u] = ~gate[n, u]
+            dz = da * gate
     return grad.astype(np.float32), loss
 
 

@@ -1,15 +1,25 @@
 """Whole Sync EASGD rounds (gradient + elastic update) on the GPU against the oracle: the three
-training workloads, free-running over all their rounds and teacher-forced per round."""
+training workloads over all their rounds, free-running and teacher-forced.
+
+A hidden unit whose pre-activation is within fp32 rounding of zero has a ReLU gate that fp32 and fp64
+arithmetic may decide differently; both gradients are valid.  The oracle side therefore resolves such
+ties per worker and per round towards the valid alternative that the GPU gradient matches
+(gpu_util.match_gradient enumerates the oracle's own near-zero units); everything else is unique and is
+compared at the stated tolerance."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 import workloads
-from gpu_util import HUNDRED_ROUND_TOL, PER_ROUND_TOL, normwise, to_dev, to_host
+from gpu_util import (HUNDRED_ROUND_TOL, PER_ROUND_TOL, match_gradients_all_workers, normwise, to_dev, to_host)
 
 pytestmark = pytest.mark.gpu
 F = np.float32
+# free-running: the two trajectories already differ by rounding when their gradients are matched, so both
+# the match tolerance and the "near zero" band of the ReLU gates are wider than in the teacher-forced check
+FREE_RUNNING_MATCH_TOL = 5e-5
+FREE_RUNNING_NEAR_REL = 4e-5
 
 
 @pytest.fixture(scope="module")
@@ -19,13 +29,11 @@ def hip():
     return hip
 
 
-def _oracle_round(wl, W, V, Wc, X, y):
-    G, loss = oracle.mlp_grad_all_workers(wl.dims, W, X, y)
+def _oracle_update(wl, W, V, Wc, G):
     if wl.momentum:
         oracle.measgd_round(W, V, G, Wc, F(wl.eta), F(wl.rho), F(wl.delta), N=wl.N)
     else:
         oracle.easgd_round(W, G, Wc, F(wl.eta), F(wl.rho), N=wl.N)
-    return loss
 
 
 def _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws):
@@ -46,29 +54,40 @@ def test_training_rounds(hip, name, rounds, forced_every):
     V = np.zeros_like(W); V[:, wl.N:] = np.nan
     dW, dWc, dV = to_dev(W), to_dev(Wc), to_dev(V)
     dG = torch.full_like(dW, float("nan"))
+    fG = torch.full_like(dW, float("nan"))
     ws = torch.empty(hip.easgd_grad_workspace_bytes(wl.dims, wl.P, wl.batch), dtype=torch.uint8, device="cuda")
-    worst_forced = 0.0
-    first_loss = last_loss = None
+    worst_forced, ties = 0.0, 0
+    losses = []
     for t in range(rounds):
         X, y = workloads.minibatch(wl, t)
         dX, dy = to_dev(X), to_dev(y)
-        forced = (t % forced_every == 0) or t == rounds - 1
-        if forced:      # one GPU round started from the oracle's state of this round
+        if (t % forced_every == 0) or t == rounds - 1:
+            # teacher-forced: one GPU round started from the oracle's state of this round
             fW, fWc, fV = to_dev(W), to_dev(Wc), to_dev(V)
-            _gpu_round(hip, wl, fW, fV, fWc, dG, dX, dy, ws)
-        _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws)
-        loss = _oracle_round(wl, W, V, Wc, X, y)
-        first_loss = loss.mean() if first_loss is None else first_loss
-        last_loss = loss.mean()
-        if forced:
-            worst_forced = max(worst_forced, normwise(to_host(fW), W), normwise(to_host(fWc), Wc))
+            _gpu_round(hip, wl, fW, fV, fWc, fG, dX, dy, ws)
+            Gf, _, k = match_gradients_all_workers(to_host(fG), wl.dims, W, X, y, PER_ROUND_TOL)
+            ties += k
+            W1, V1, Wc1 = W.copy(), V.copy(), Wc.copy()
+            _oracle_update(wl, W1, V1, Wc1, Gf)
+            worst_forced = max(worst_forced, normwise(to_host(fW), W1), normwise(to_host(fWc), Wc1))
             if wl.momentum:
-                worst_forced = max(worst_forced, normwise(to_host(fV), V))
+                worst_forced = max(worst_forced, normwise(to_host(fV), V1))
+        # free-running: both sides continue from their own state
+        _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws)
+        G, loss, k = match_gradients_all_workers(to_host(dG), wl.dims, W, X, y, FREE_RUNNING_MATCH_TOL,
+                                                 FREE_RUNNING_NEAR_REL)
+        ties += k
+        print(f"  round {t}: {k} gate tie(s)", flush=True)
+        _oracle_update(wl, W, V, Wc, G)
+        losses.append(loss.mean())
         if t == 0:      # identical start: the center does not move in the first round
             np.testing.assert_array_equal(to_host(dWc), w0)
+    print(f"{name}: {ties} near-zero ReLU gate(s) resolved; teacher-forced worst {worst_forced:.2e}; "
+          f"free-running W {normwise(to_host(dW), W):.2e} Wc {normwise(to_host(dWc), Wc):.2e}; "
+          f"loss {losses[0]:.4f} -> {losses[-1]:.4f}")
     assert worst_forced <= PER_ROUND_TOL
     assert normwise(to_host(dW), W) <= HUNDRED_ROUND_TOL
     assert normwise(to_host(dWc), Wc) <= HUNDRED_ROUND_TOL
     if wl.momentum:
         assert normwise(to_host(dV), V) <= HUNDRED_ROUND_TOL
-    assert np.isfinite(last_loss) and np.isfinite(first_loss)
+    assert np.isfinite(losses).all()

@@ -143,3 +143,22 @@ def test_last_bias_gradient_sums_to_zero_and_workers_are_independent():
     g1, l1 = oracle.mlp_grad(wl.dims, W[1], X[1], y[1])
     np.testing.assert_array_equal(G[1, :wl.N], g1)
     assert loss[1] == l1
+
+
+def test_near_zero_gates_are_reported_and_flippable():
+    """A hidden unit with pre-activation exactly 0 is a tie of the ReLU gate: the oracle reports it,
+    and flipping its gate changes the gradient by that unit's back-propagated signal only."""
+    dims = (3, 2, 2)
+    w = np.array([1, 0, -1, 1, 0, 1, 0, 0,      # W0 (3x2), b0
+                  1, -1, 2, 1, 0, 0], dtype=F)   # W1 (2x2), b1
+    X = np.array([[2, 2, 1], [1, 1, 1]], dtype=F)   # sample 0: z = (0, 3); sample 1: z = (0, 2)
+    y = np.array([0, 1], dtype=np.int32)
+    near = []
+    g0, _ = oracle.mlp_grad(dims, w, X, y, near_zero=near, near_zero_rel=1e-9)
+    assert near == [(0, 0, 0), (0, 1, 0)]
+    g1, _ = oracle.mlp_grad(dims, w, X, y, gate_flips=[(0, 0, 0)])
+    changed = np.nonzero(g0 != g1)[0]
+    # only column 0 of W0 (packed indices 0, 2, 4) and b0[0] (index 6) may change
+    assert set(changed) <= {0, 2, 4, 6} and len(changed) > 0
+    # gate closed (default, z == 0): no signal reaches column 0 from either sample
+    assert g0[0] == 0 and g0[6] == 0

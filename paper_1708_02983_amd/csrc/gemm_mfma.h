@@ -17,7 +17,7 @@
 // wavefront owns (BM/WAVES_M) x (BN/WAVES_N) of it as 32x32 MFMA accumulators.
 // K is walked in slabs of BK: the next slab travels global -> registers while the
 // current one is multiplied out of LDS, then registers -> the other LDS buffer.
-// LDS holds both operands k-major ([k][m] and [k][n], row pitch +4 floats) so an
+// LDS holds both operands k-major ([k][m] and [k][n], padded row pitch) so an
 // MFMA operand fetch is one conflict-free ds_read_b32 per lane.
 #pragma once
 #include "common.h"
@@ -68,7 +68,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
     constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int PITCH_A = BM + 4, PITCH_B = BN + 4;
+    // LDS row pitch: +4 keeps 128-bit row stores aligned for operands that arrive m/n-contiguous; operands that
+    // arrive k-contiguous are scattered as scalars (lane -> k quad fastest), which is conflict-free when
+    // 4*pitch = 32/(BK/4) mod 32, i.e. pitch = 1 mod 8 for BK = 32 and pitch = 2 mod 8 for BK = 16
+    constexpr int PAD_K = (BK == 32) ? 1 : 2;
+    constexpr int PITCH_A = BM + (A_LAYOUT == K_CONTIG ? PAD_K : 4), PITCH_B = BN + (B_LAYOUT == K_CONTIG ? PAD_K : 4);
+    static_assert(BK == 16 || BK == 32, "slab depth");
+    static_assert(BM % 8 == 0 && BN % 8 == 0, "tile shape");
     constexpr int CHUNKS_A = BM * BK / 4, CHUNKS_B = BN * BK / 4;
     constexpr int IT_A = (CHUNKS_A + NTHREADS - 1) / NTHREADS, IT_B = (CHUNKS_B + NTHREADS - 1) / NTHREADS;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 4 == 0, "tile shape");
@@ -95,29 +101,82 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
 
     f32x4 ra[IT_A], rb[IT_B];
 
+    // Global -> registers for the slab that starts at k0.  Interior slabs (every 128-bit chunk of the
+    // tile lies inside the stored extent of its row, decided per block, not per lane) issue plain
+    // vector loads back to back: rows outside the matrix are clamped to the last row and zeroed after
+    // the load, so no lane diverges and no load waits for another.  Edge slabs take the guarded path.
+    const int a_clamp = (A_LAYOUT == K_CONTIG) ? p.M - 1 : 0, b_clamp = (B_LAYOUT == K_CONTIG) ? p.N - 1 : 0;
     auto load_global = [&](int k0) {
+        const bool a_interior = VEC && ((A_LAYOUT == K_CONTIG) ? (k0 + BK <= min(p.a_lim, k_end))
+                                                               : (k0 + BK <= k_end && m0 + BM <= p.a_lim));
+        const bool b_interior = VEC && ((B_LAYOUT == K_CONTIG) ? (k0 + BK <= min(b_lim, k_end))
+                                                               : (k0 + BK <= k_end && n0 + BN <= b_lim));
+        if (a_interior) {
 #pragma unroll
-        for (int it = 0; it < IT_A; ++it) {
-            const int c = tid + it * NTHREADS;
-            if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
-            if (A_LAYOUT == K_CONTIG) {
-                const int kq = c % (BK / 4), m = m0 + c / (BK / 4);
-                ra[it] = fetch4<VEC>(A + (size_t)m * p.lda, k0 + 4 * kq, min(p.a_lim, k_end), p.a_ones < k_end ? p.a_ones : -1, m < p.M);
-            } else {
-                const int mq = c % (BM / 4), k = k0 + c / (BM / 4);
-                ra[it] = fetch4<VEC>(A + (size_t)k * p.lda, m0 + 4 * mq, p.a_lim, p.a_ones, k < k_end);
+            for (int it = 0; it < IT_A; ++it) {
+                const int c = tid + it * NTHREADS;
+                if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
+                if (A_LAYOUT == K_CONTIG) {
+                    const int kq = c % (BK / 4), m = m0 + c / (BK / 4);
+                    ra[it] = *reinterpret_cast<const f32x4 *>(A + (size_t)min(m, a_clamp) * p.lda + k0 + 4 * kq);
+                } else {
+                    const int mq = c % (BM / 4), k = k0 + c / (BM / 4);
+                    ra[it] = *reinterpret_cast<const f32x4 *>(A + (size_t)k * p.lda + m0 + 4 * mq);
+                }
+            }
+            if (A_LAYOUT == K_CONTIG && m0 + BM > p.M) {
+#pragma unroll
+                for (int it = 0; it < IT_A; ++it) {
+                    const int c = tid + it * NTHREADS;
+                    if (m0 + c / (BK / 4) >= p.M) ra[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < IT_A; ++it) {
+                const int c = tid + it * NTHREADS;
+                if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
+                if (A_LAYOUT == K_CONTIG) {
+                    const int kq = c % (BK / 4), m = m0 + c / (BK / 4);
+                    ra[it] = fetch4<VEC>(A + (size_t)m * p.lda, k0 + 4 * kq, min(p.a_lim, k_end), p.a_ones < k_end ? p.a_ones : -1, m < p.M);
+                } else {
+                    const int mq = c % (BM / 4), k = k0 + c / (BM / 4);
+                    ra[it] = fetch4<VEC>(A + (size_t)k * p.lda, m0 + 4 * mq, p.a_lim, p.a_ones, k < k_end);
+                }
             }
         }
+        if (b_interior) {
 #pragma unroll
-        for (int it = 0; it < IT_B; ++it) {
-            const int c = tid + it * NTHREADS;
-            if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
-            if (B_LAYOUT == K_CONTIG) {
-                const int kq = c % (BK / 4), n = n0 + c / (BK / 4);
-                rb[it] = fetch4<VEC>(B + (size_t)n * p.ldb, k0 + 4 * kq, min(b_lim, k_end), -1, n < p.N);
-            } else {
-                const int nq = c % (BN / 4), k = k0 + c / (BN / 4);
-                rb[it] = fetch4<VEC>(B + (size_t)k * p.ldb, n0 + 4 * nq, b_lim, -1, k < k_end);
+            for (int it = 0; it < IT_B; ++it) {
+                const int c = tid + it * NTHREADS;
+                if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
+                if (B_LAYOUT == K_CONTIG) {
+                    const int kq = c % (BK / 4), n = n0 + c / (BK / 4);
+                    rb[it] = *reinterpret_cast<const f32x4 *>(B + (size_t)min(n, b_clamp) * p.ldb + k0 + 4 * kq);
+                } else {
+                    const int nq = c % (BN / 4), k = k0 + c / (BN / 4);
+                    rb[it] = *reinterpret_cast<const f32x4 *>(B + (size_t)k * p.ldb + n0 + 4 * nq);
+                }
+            }
+            if (B_LAYOUT == K_CONTIG && n0 + BN > p.N) {
+#pragma unroll
+                for (int it = 0; it < IT_B; ++it) {
+                    const int c = tid + it * NTHREADS;
+                    if (n0 + c / (BK / 4) >= p.N) rb[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < IT_B; ++it) {
+                const int c = tid + it * NTHREADS;
+                if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
+                if (B_LAYOUT == K_CONTIG) {
+                    const int kq = c % (BK / 4), n = n0 + c / (BK / 4);
+                    rb[it] = fetch4<VEC>(B + (size_t)n * p.ldb, k0 + 4 * kq, min(b_lim, k_end), -1, n < p.N);
+                } else {
+                    const int nq = c % (BN / 4), k = k0 + c / (BN / 4);
+                    rb[it] = fetch4<VEC>(B + (size_t)k * p.ldb, n0 + 4 * nq, b_lim, -1, k < k_end);
+                }
             }
         }
     };

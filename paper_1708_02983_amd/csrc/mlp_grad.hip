@@ -25,7 +25,7 @@ struct GradPlan {
     size_t N = 0;
     size_t off[MAX_LAYERS] = {0};       // packed offset of layer l
     size_t act_off[MAX_LAYERS] = {0};   // workspace offset (bytes) of A_l, l = 1..L-1
-    size_t logits_off = 0, dz_off[2] = {0, 0};
+    size_t logits_off = 0, rowloss_off = 0, dz_off[2] = {0, 0};
     size_t bytes = 0;
     int splits = 1, k_per_split = 0;
 };
@@ -61,6 +61,8 @@ static bool make_plan(const int *dims, int L, int P, int b, GradPlan &pl)
     for (int l = 1; l <= L; ++l) widest = dims[l] > (int)widest ? dims[l] : widest;
     pl.logits_off = o;
     o += align_up((size_t)pl.splits * P * b * dims[L] * sizeof(float), 256);
+    pl.rowloss_off = o;
+    o += align_up((size_t)P * b * sizeof(float), 256);
     for (int q = 0; q < 2; ++q) {
         pl.dz_off[q] = o;
         o += align_up((size_t)P * b * widest * sizeof(float), 256);
@@ -69,62 +71,66 @@ static bool make_plan(const int *dims, int L, int P, int b, GradPlan &pl)
     return true;
 }
 
-// Softmax cross-entropy on the logits of all workers.  One block per worker; each
-// of its wavefronts walks rows wave, wave+4, ... and handles one row at a time with
-// the classes spread over the lanes.  Sums use fixed shuffle trees and fixed orders.
-//   zpart [splits][P*b][C] partial logits;  dz [P*b][C] <- (softmax - onehot)/b;  loss[P] <- mean
+// Softmax cross-entropy on the logits of all workers: one wavefront per sample row, the classes
+// spread over the lanes.  Sums use fixed shuffle trees and fixed orders.
+//   zpart [splits][rows][C] partial logits (added in ascending split order)
+//   dz [rows][C] <- (softmax - onehot)/b;   row_loss[rows] <- -log softmax(label)
 __global__ __launch_bounds__(256) void softmax_xent_kernel(const float *__restrict__ zpart, const int *__restrict__ y,
-                                                           float *__restrict__ dz, float *__restrict__ loss,
-                                                           int b, int C, int splits, size_t split_stride)
+                                                           float *__restrict__ dz, float *__restrict__ row_loss,
+                                                           int rows, int b, int C, int splits, size_t split_stride)
 {
-    __shared__ float wave_loss[4];
-    const int w = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= (size_t)rows) return;
     const float inv_b = 1.0f / (float)b;
-    float my_loss = 0.f;
-    for (int r = wave; r < b; r += 4) {
-        const size_t row = (size_t)w * b + r;
-        const int label = y[row];
-        // up to MAX_CLASSES/64 = 16 classes per lane
-        float z[MAX_CLASSES / 64];
-        float zmax = -INFINITY;
+    const int label = y[row];
+    float z[MAX_CLASSES / 64];               // up to 16 classes per lane
+    float zmax = -INFINITY;
 #pragma unroll
-        for (int q = 0; q < MAX_CLASSES / 64; ++q) {
-            const int c = lane + 64 * q;
-            float v = -INFINITY;
-            if (c < C) {
-                v = 0.f;
-                for (int s = 0; s < splits; ++s) v += zpart[s * split_stride + row * C + c];
-            }
-            z[q] = v;
-            zmax = fmaxf(zmax, v);
+    for (int q = 0; q < MAX_CLASSES / 64; ++q) {
+        const int c = lane + 64 * q;
+        float v = -INFINITY;
+        if (c < C) {
+            v = 0.f;
+            for (int s = 0; s < splits; ++s) v += zpart[s * split_stride + row * C + c];
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o));
-        float sum = 0.f, zlabel = 0.f;      // zlabel: shifted logit of the true class (one lane holds it)
-#pragma unroll
-        for (int q = 0; q < MAX_CLASSES / 64; ++q) {
-            const int c = lane + 64 * q;
-            if (c < C) {
-                if (c == label) zlabel = z[q] - zmax;
-                z[q] = expf(z[q] - zmax);
-                sum += z[q];
-            }
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) zlabel += __shfl_xor(zlabel, o);
-        const float inv_sum = 1.0f / sum;
-#pragma unroll
-        for (int q = 0; q < MAX_CLASSES / 64; ++q) {
-            const int c = lane + 64 * q;
-            if (c < C) dz[row * C + c] = (z[q] * inv_sum - (c == label ? 1.f : 0.f)) * inv_b;
-        }
-        my_loss += logf(sum) - zlabel;      // -log softmax(label)
+        z[q] = v;
+        zmax = fmaxf(zmax, v);
     }
-    if (lane == 0) wave_loss[wave] = my_loss;
-    __syncthreads();
-    if (threadIdx.x == 0 && loss) loss[w] = (((wave_loss[0] + wave_loss[1]) + wave_loss[2]) + wave_loss[3]) * inv_b;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o));
+    float sum = 0.f, zlabel = 0.f;           // zlabel: shifted logit of the true class (one lane holds it)
+#pragma unroll
+    for (int q = 0; q < MAX_CLASSES / 64; ++q) {
+        const int c = lane + 64 * q;
+        if (c < C) {
+            if (c == label) zlabel = z[q] - zmax;
+            z[q] = expf(z[q] - zmax);
+            sum += z[q];
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) zlabel += __shfl_xor(zlabel, o);
+    const float inv_sum = 1.0f / sum;
+#pragma unroll
+    for (int q = 0; q < MAX_CLASSES / 64; ++q) {
+        const int c = lane + 64 * q;
+        if (c < C) dz[row * C + c] = (z[q] * inv_sum - (c == label ? 1.f : 0.f)) * inv_b;
+    }
+    if (lane == 0) row_loss[row] = logf(sum) - zlabel;
+}
+
+// loss[w] = mean of the worker's b row losses: lane l adds rows l, l+64, ... in order, then a fixed shuffle tree.
+__global__ __launch_bounds__(64) void mean_loss_kernel(const float *__restrict__ row_loss, float *__restrict__ loss, int b)
+{
+    const int w = blockIdx.x, lane = threadIdx.x;
+    float acc = 0.f;
+    for (int r = lane; r < b; r += 64) acc += row_loss[(size_t)w * b + r];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) loss[w] = acc / (float)b;
 }
 
 // ---- GEMM dispatch -------------------------------------------------------
@@ -221,8 +227,11 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
         if (last) launch_gemm<K_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, s);
         else launch_gemm<K_CONTIG, MN_CONTIG, EPI_RELU>(a, vec, s);
     }
-    hipLaunchKernelGGL(softmax_xent_kernel, dim3(P), dim3(256), 0, s, logits, y, dz[(L - 1) & 1], loss, b, dims[L],
-                       pl.splits, (size_t)P * b * dims[L]);
+    float *row_loss = reinterpret_cast<float *>(ws + pl.rowloss_off);
+    const int rows = P * b;
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) & 1], row_loss,
+                       rows, b, dims[L], pl.splits, (size_t)rows * dims[L]);
+    if (loss) hipLaunchKernelGGL(mean_loss_kernel, dim3(P), dim3(64), 0, s, row_loss, loss, b);
 
     // ---- backward propagation ----
     for (int l = L - 1; l >= 0; --l) {

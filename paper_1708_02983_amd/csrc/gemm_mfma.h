@@ -15,8 +15,8 @@
 //
 // Tiling: a block of WAVES_M x WAVES_N wavefronts owns a BM x BN tile of C; each
 // wavefront owns (BM/WAVES_M) x (BN/WAVES_N) of it as 32x32 MFMA accumulators.
-// K is walked in slabs of BK: the next slab travels global -> registers while the
-// current one is multiplied out of LDS, then registers -> the other LDS buffer.
+// K is walked in slabs of BK with a prefetch distance of two slabs: global ->
+// registers (two stages) -> LDS (two buffers) -> MFMA operands.
 // LDS holds both operands k-major ([k][m] and [k][n], padded row pitch) so an
 // MFMA operand fetch is one conflict-free ds_read_b32 per lane.
 #pragma once
@@ -99,100 +99,67 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WAVES_N) * WTM, wn0 = (wave % WAVES_N) * WTN;
 
-    f32x4 ra[IT_A], rb[IT_B];
+    // ---- per-thread loader geometry (constant over the K loop) ----
+    // chunk c = tid + it*NTHREADS is four consecutive elements along the operand's contiguous axis
+    const float *a_src[IT_A], *b_src[IT_B];   // source of the chunk in the slab that starts at k = 0
+    int a_dst[IT_A], b_dst[IT_B];             // LDS offset of the chunk's first element
+    bool a_ok[IT_A], b_ok[IT_B];              // false: the row lies outside the matrix, store zeros
+#pragma unroll
+    for (int it = 0; it < IT_A; ++it) {
+        const int c = tid + it * NTHREADS;
+        if (A_LAYOUT == K_CONTIG) {
+            const int kq = c % (BK / 4), m = c / (BK / 4);
+            a_ok[it] = (m0 + m < p.M);
+            a_src[it] = A + (size_t)min(m0 + m, p.M - 1) * p.lda + 4 * kq;
+            a_dst[it] = 4 * kq * PITCH_A + m;
+        } else {
+            const int mq = c % (BM / 4), k = c / (BM / 4);
+            a_ok[it] = true;
+            a_src[it] = A + (size_t)k * p.lda + m0 + 4 * mq;
+            a_dst[it] = k * PITCH_A + 4 * mq;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < IT_B; ++it) {
+        const int c = tid + it * NTHREADS;
+        if (B_LAYOUT == K_CONTIG) {
+            const int kq = c % (BK / 4), n = c / (BK / 4);
+            b_ok[it] = (n0 + n < p.N);
+            b_src[it] = B + (size_t)min(n0 + n, p.N - 1) * p.ldb + 4 * kq;
+            b_dst[it] = 4 * kq * PITCH_B + n;
+        } else {
+            const int nq = c % (BN / 4), k = c / (BN / 4);
+            b_ok[it] = true;
+            b_src[it] = B + (size_t)k * p.ldb + n0 + 4 * nq;
+            b_dst[it] = k * PITCH_B + 4 * nq;
+        }
+    }
+    const size_t a_kstep = (A_LAYOUT == K_CONTIG) ? 1 : (size_t)p.lda;   // address step per unit of k
+    const size_t b_kstep = (B_LAYOUT == K_CONTIG) ? 1 : (size_t)p.ldb;
 
-    // Global -> registers for the slab that starts at k0.  Interior slabs (every 128-bit chunk of the
-    // tile lies inside the stored extent of its row, decided per block, not per lane) issue plain
-    // vector loads back to back: rows outside the matrix are clamped to the last row and zeroed after
-    // the load, so no lane diverges and no load waits for another.  Edge slabs take the guarded path.
-    const int a_clamp = (A_LAYOUT == K_CONTIG) ? p.M - 1 : 0, b_clamp = (B_LAYOUT == K_CONTIG) ? p.N - 1 : 0;
-    auto load_global = [&](int k0) {
-        const bool a_interior = VEC && ((A_LAYOUT == K_CONTIG) ? (k0 + BK <= min(p.a_lim, k_end))
-                                                               : (k0 + BK <= k_end && m0 + BM <= p.a_lim));
-        const bool b_interior = VEC && ((B_LAYOUT == K_CONTIG) ? (k0 + BK <= min(b_lim, k_end))
-                                                               : (k0 + BK <= k_end && n0 + BN <= b_lim));
-        if (a_interior) {
+    // Interior slabs: plain 128-bit loads, no lane diverges (rows outside the matrix were clamped above).
+    auto load_fast = [&](int k0, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
 #pragma unroll
-            for (int it = 0; it < IT_A; ++it) {
-                const int c = tid + it * NTHREADS;
-                if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
-                if (A_LAYOUT == K_CONTIG) {
-                    const int kq = c % (BK / 4), m = m0 + c / (BK / 4);
-                    ra[it] = *reinterpret_cast<const f32x4 *>(A + (size_t)min(m, a_clamp) * p.lda + k0 + 4 * kq);
-                } else {
-                    const int mq = c % (BM / 4), k = k0 + c / (BM / 4);
-                    ra[it] = *reinterpret_cast<const f32x4 *>(A + (size_t)k * p.lda + m0 + 4 * mq);
-                }
-            }
-            if (A_LAYOUT == K_CONTIG && m0 + BM > p.M) {
+        for (int it = 0; it < IT_A; ++it)
+            if (CHUNKS_A % NTHREADS == 0 || tid + it * NTHREADS < CHUNKS_A)
+                ra[it] = *reinterpret_cast<const f32x4 *>(a_src[it] + (size_t)k0 * a_kstep);
 #pragma unroll
-                for (int it = 0; it < IT_A; ++it) {
-                    const int c = tid + it * NTHREADS;
-                    if (m0 + c / (BK / 4) >= p.M) ra[it] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < IT_A; ++it) {
-                const int c = tid + it * NTHREADS;
-                if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
-                if (A_LAYOUT == K_CONTIG) {
-                    const int kq = c % (BK / 4), m = m0 + c / (BK / 4);
-                    ra[it] = fetch4<VEC>(A + (size_t)m * p.lda, k0 + 4 * kq, min(p.a_lim, k_end), p.a_ones < k_end ? p.a_ones : -1, m < p.M);
-                } else {
-                    const int mq = c % (BM / 4), k = k0 + c / (BM / 4);
-                    ra[it] = fetch4<VEC>(A + (size_t)k * p.lda, m0 + 4 * mq, p.a_lim, p.a_ones, k < k_end);
-                }
-            }
-        }
-        if (b_interior) {
-#pragma unroll
-            for (int it = 0; it < IT_B; ++it) {
-                const int c = tid + it * NTHREADS;
-                if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
-                if (B_LAYOUT == K_CONTIG) {
-                    const int kq = c % (BK / 4), n = n0 + c / (BK / 4);
-                    rb[it] = *reinterpret_cast<const f32x4 *>(B + (size_t)min(n, b_clamp) * p.ldb + k0 + 4 * kq);
-                } else {
-                    const int nq = c % (BN / 4), k = k0 + c / (BN / 4);
-                    rb[it] = *reinterpret_cast<const f32x4 *>(B + (size_t)k * p.ldb + n0 + 4 * nq);
-                }
-            }
-            if (B_LAYOUT == K_CONTIG && n0 + BN > p.N) {
-#pragma unroll
-                for (int it = 0; it < IT_B; ++it) {
-                    const int c = tid + it * NTHREADS;
-                    if (n0 + c / (BK / 4) >= p.N) rb[it] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < IT_B; ++it) {
-                const int c = tid + it * NTHREADS;
-                if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
-                if (B_LAYOUT == K_CONTIG) {
-                    const int kq = c % (BK / 4), n = n0 + c / (BK / 4);
-                    rb[it] = fetch4<VEC>(B + (size_t)n * p.ldb, k0 + 4 * kq, min(b_lim, k_end), -1, n < p.N);
-                } else {
-                    const int nq = c % (BN / 4), k = k0 + c / (BN / 4);
-                    rb[it] = fetch4<VEC>(B + (size_t)k * p.ldb, n0 + 4 * nq, b_lim, -1, k < k_end);
-                }
-            }
-        }
+        for (int it = 0; it < IT_B; ++it)
+            if (CHUNKS_B % NTHREADS == 0 || tid + it * NTHREADS < CHUNKS_B)
+                rb[it] = *reinterpret_cast<const f32x4 *>(b_src[it] + (size_t)k0 * b_kstep);
     };
-
-    auto store_lds = [&](int buf) {
+    // Edge slabs and edge tiles: every element guarded (zero fill, ones vector).
+    auto load_guarded = [&](int k0, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
 #pragma unroll
         for (int it = 0; it < IT_A; ++it) {
             const int c = tid + it * NTHREADS;
             if (CHUNKS_A % NTHREADS != 0 && c >= CHUNKS_A) continue;
             if (A_LAYOUT == K_CONTIG) {
-                const int kq = c % (BK / 4), m = c / (BK / 4);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) As[buf][(4 * kq + q) * PITCH_A + m] = ra[it][q];
+                const int kq = c % (BK / 4), m = m0 + c / (BK / 4);
+                ra[it] = fetch4<VEC>(A + (size_t)m * p.lda, k0 + 4 * kq, min(p.a_lim, k_end), p.a_ones < k_end ? p.a_ones : -1, m < p.M);
             } else {
-                const int mq = c % (BM / 4), k = c / (BM / 4);
-                *reinterpret_cast<f32x4 *>(&As[buf][k * PITCH_A + 4 * mq]) = ra[it];
+                const int mq = c % (BM / 4), k = k0 + c / (BM / 4);
+                ra[it] = fetch4<VEC>(A + (size_t)k * p.lda, m0 + 4 * mq, p.a_lim, p.a_ones, k < k_end);
             }
         }
 #pragma unroll
@@ -200,12 +167,38 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
             const int c = tid + it * NTHREADS;
             if (CHUNKS_B % NTHREADS != 0 && c >= CHUNKS_B) continue;
             if (B_LAYOUT == K_CONTIG) {
-                const int kq = c % (BK / 4), n = c / (BK / 4);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) Bs[buf][(4 * kq + q) * PITCH_B + n] = rb[it][q];
+                const int kq = c % (BK / 4), n = n0 + c / (BK / 4);
+                rb[it] = fetch4<VEC>(B + (size_t)n * p.ldb, k0 + 4 * kq, min(b_lim, k_end), -1, n < p.N);
             } else {
-                const int nq = c % (BN / 4), k = c / (BN / 4);
-                *reinterpret_cast<f32x4 *>(&Bs[buf][k * PITCH_B + 4 * nq]) = rb[it];
+                const int nq = c % (BN / 4), k = k0 + c / (BN / 4);
+                rb[it] = fetch4<VEC>(B + (size_t)k * p.ldb, n0 + 4 * nq, b_lim, -1, k < k_end);
+            }
+        }
+    };
+
+    auto store_lds = [&](int buf, const f32x4 (&ra)[IT_A], const f32x4 (&rb)[IT_B], bool zero_rows) {
+#pragma unroll
+        for (int it = 0; it < IT_A; ++it) {
+            if (CHUNKS_A % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_A) continue;
+            f32x4 v = ra[it];
+            if (A_LAYOUT == K_CONTIG) {
+                if (zero_rows && !a_ok[it]) v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) As[buf][a_dst[it] + q * PITCH_A] = v[q];
+            } else {
+                *reinterpret_cast<f32x4 *>(&As[buf][a_dst[it]]) = v;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT_B; ++it) {
+            if (CHUNKS_B % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_B) continue;
+            f32x4 v = rb[it];
+            if (B_LAYOUT == K_CONTIG) {
+                if (zero_rows && !b_ok[it]) v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) Bs[buf][b_dst[it] + q * PITCH_B] = v[q];
+            } else {
+                *reinterpret_cast<f32x4 *>(&Bs[buf][b_dst[it]]) = v;
             }
         }
     };
@@ -218,42 +211,102 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int n_slabs = (k_end - k_begin + BK - 1) / BK;
-    if (n_slabs > 0) {
-        load_global(k_begin);
-        store_lds(0);
-    }
-    __syncthreads();
-
     // MFMA operand fetch: lane l supplies A[m = l%32][k = l/32] and B[k = l/32][n = l%32]
     const int frag_k = lane >> 5, frag_x = lane & 31;
-    for (int s = 0; s < n_slabs; ++s) {
-        const int buf = s & 1;
-        const bool more = (s + 1 < n_slabs);
-        if (more) load_global(k_begin + (s + 1) * BK);
+    // multiply the slab held in LDS buffer `buf`; k_left = number of valid k in it
+    auto multiply_slab = [&](int buf, int k_left) {
         const float *as = &As[buf][frag_k * PITCH_A + wm0 + frag_x];
         const float *bs = &Bs[buf][frag_k * PITCH_B + wn0 + frag_x];
-        auto multiply = [&](int kk) {
-            float a[TM], b[TN];
+        auto fetch = [&](int kk, float (&a)[TM], float (&b)[TN]) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) a[i] = as[kk * PITCH_A + i * 32];
 #pragma unroll
             for (int j = 0; j < TN; ++j) b[j] = bs[kk * PITCH_B + j * 32];
+        };
+        auto multiply = [&](const float (&a)[TM], const float (&b)[TN]) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         };
-        const int k_left = k_end - (k_begin + s * BK);
         if (k_left >= BK) {
+            // operands of k pair kk+2 are fetched from LDS before the MFMAs of pair kk are issued,
+            // so the LDS latency hides behind the matrix pipeline
+            float a[2][TM], b[2][TN];
+            fetch(0, a[0], b[0]);
 #pragma unroll
-            for (int kk = 0; kk < BK; kk += 2) multiply(kk);
+            for (int kk = 0; kk < BK; kk += 2) {
+                const int cur = (kk >> 1) & 1;
+                if (kk + 2 < BK) fetch(kk + 2, a[cur ^ 1], b[cur ^ 1]);
+                __builtin_amdgcn_sched_barrier(0);      // keep the LDS reads ahead of the MFMAs below
+                multiply(a[cur], b[cur]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         } else {
-            // short last slab: stop at the last k pair that holds data (the rest of the slab is zero)
-            for (int kk = 0; kk < k_left; kk += 2) multiply(kk);
+            // short slab: stop at the last k pair that holds data (the rest of the slab is zero)
+            for (int kk = 0; kk < k_left; kk += 2) {
+                float a[TM], b[TN];
+                fetch(kk, a, b);
+                multiply(a, b);
+            }
         }
-        if (more) store_lds(buf ^ 1);
+    };
+
+    // Leading slabs that lie fully inside the stored extent of both operands (decided per block).
+    const int n_slabs = (k_end - k_begin + BK - 1) / BK;
+    int n_fast = 0;
+    {
+        const bool tile_ok = VEC && (A_LAYOUT == K_CONTIG || m0 + BM <= p.a_lim) && (B_LAYOUT == K_CONTIG || n0 + BN <= b_lim);
+        int k_lim = k_end;
+        if (A_LAYOUT == K_CONTIG) k_lim = min(k_lim, p.a_lim);
+        if (B_LAYOUT == K_CONTIG) k_lim = min(k_lim, b_lim);
+        if (tile_ok && k_lim > k_begin) n_fast = (k_lim - k_begin) / BK;
+    }
+
+    // Two register stages R0/R1 and two LDS buffers: slab s sits in stage s%2 while in flight and in LDS
+    // buffer s%2 while it is multiplied.  In the steady state the loads of slab s+2 are issued, slab s is
+    // multiplied, then slab s+1 moves registers -> LDS: a prefetch distance of two slabs, one barrier per slab.
+    f32x4 ra0[IT_A], rb0[IT_B], ra1[IT_A], rb1[IT_B];
+    int s_done = 0;
+    if (n_fast >= 2) {
+        load_fast(k_begin, ra0, rb0);
+        load_fast(k_begin + BK, ra1, rb1);
+        store_lds(0, ra0, rb0, true);
+        __syncthreads();
+        int s = 0;
+        for (; s + 3 < n_fast; s += 2) {
+            load_fast(k_begin + (s + 2) * BK, ra0, rb0);
+            multiply_slab(0, BK);
+            store_lds(1, ra1, rb1, true);
+            __syncthreads();
+            load_fast(k_begin + (s + 3) * BK, ra1, rb1);
+            multiply_slab(1, BK);
+            store_lds(0, ra0, rb0, true);
+            __syncthreads();
+        }
+        // two or three slabs are left: s (in LDS 0), s+1 (in R1), and s+2 if n_fast is odd
+        const bool three = (s + 2 < n_fast);
+        if (three) load_fast(k_begin + (s + 2) * BK, ra0, rb0);
+        multiply_slab(0, BK);
+        store_lds(1, ra1, rb1, true);
+        __syncthreads();
+        multiply_slab(1, BK);
+        if (three) {
+            store_lds(0, ra0, rb0, true);
+            __syncthreads();
+            multiply_slab(0, BK);
+        }
+        __syncthreads();
+        s_done = n_fast;
+    }
+    // Remaining slabs (edge of K, edge tiles, unaligned operands): load, store, multiply, one at a time.
+    for (int s = s_done; s < n_slabs; ++s) {
+        const int k0 = k_begin + s * BK;
+        load_guarded(k0, ra0, rb0);
+        store_lds(0, ra0, rb0, false);
+        __syncthreads();
+        multiply_slab(0, k_end - k0);
         __syncthreads();
     }
 

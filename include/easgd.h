@@ -122,9 +122,9 @@ size_t easgd_mlp_num_params(const int *dims, int n_layers);
  * Returns EASGD_EINVAL for an unknown option or an out-of-range value.
  */
 typedef enum {
-    EASGD_OPT_UPDATE_BLOCKS_PER_CU = 1,  /* 0 = one block per 1024-element tile (default); k>0 = persistent grid of k*CUs blocks */
+    EASGD_OPT_UPDATE_BLOCKS_PER_CU = 1,  /* 0 = one block per tile (default); k>0 = persistent grid of k*CUs blocks */
     EASGD_OPT_UPDATE_NONTEMPORAL   = 2,  /* 1 = streaming (non-temporal) loads/stores for W, G, V (default), 0 = plain */
-    EASGD_OPT_UPDATE_UNROLL        = 3   /* workers whose loads are issued together: 2, 4 (default) or 8 */
+    EASGD_OPT_UPDATE_GROUPS        = 3   /* 128-bit groups per thread and worker: 1, 2 or 4 (default); tile = groups*1024 parameters */
 } easgd_option;
 
 int easgd_set_option(int option, long value);

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libeasgd_hip.so")
 EASGD_OK = 0
 OPT_UPDATE_BLOCKS_PER_CU = 1
 OPT_UPDATE_NONTEMPORAL = 2
-OPT_UPDATE_UNROLL = 3
+OPT_UPDATE_GROUPS = 3
 
 
 class EasgdError(RuntimeError):

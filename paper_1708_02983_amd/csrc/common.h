@@ -21,7 +21,7 @@ int num_cus();
 struct Options {
     long update_blocks_per_cu = 0;
     long update_nontemporal = 1;
-    long update_unroll = 4;
+    long update_groups = 4;
 };
 Options &options();
 

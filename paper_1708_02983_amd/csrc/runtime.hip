@@ -57,9 +57,9 @@ int easgd_set_option(int option, long value)
         if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "nontemporal must be 0 or 1, got %ld", value);
         o.update_nontemporal = value;
         return EASGD_OK;
-    case EASGD_OPT_UPDATE_UNROLL:
-        if (value != 2 && value != 4 && value != 8) return easgd::fail(EASGD_EINVAL, "unroll must be 2, 4 or 8, got %ld", value);
-        o.update_unroll = value;
+    case EASGD_OPT_UPDATE_GROUPS:
+        if (value != 1 && value != 2 && value != 4) return easgd::fail(EASGD_EINVAL, "groups must be 1, 2 or 4, got %ld", value);
+        o.update_groups = value;
         return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
@@ -72,7 +72,7 @@ long easgd_get_option(int option)
     switch (option) {
     case EASGD_OPT_UPDATE_BLOCKS_PER_CU: return o.update_blocks_per_cu;
     case EASGD_OPT_UPDATE_NONTEMPORAL: return o.update_nontemporal;
-    case EASGD_OPT_UPDATE_UNROLL: return o.update_unroll;
+    case EASGD_OPT_UPDATE_GROUPS: return o.update_groups;
     default: return -1;
     }
 }

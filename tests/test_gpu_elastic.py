@@ -119,10 +119,10 @@ def test_bitwise_reproducible_and_independent_of_launch_shape(hip):
     results = []
     saved = [hip.get_option(o) for o in (1, 2, 3)]
     try:
-        for blocks_per_cu, nt, unroll in [(0, 1, 4), (0, 1, 4), (4, 0, 2), (1, 1, 8), (8, 0, 4)]:
+        for blocks_per_cu, nt, groups in [(0, 1, 4), (0, 1, 4), (4, 0, 2), (1, 1, 1), (8, 0, 4)]:
             hip.set_option(hip.OPT_UPDATE_BLOCKS_PER_CU, blocks_per_cu)
             hip.set_option(hip.OPT_UPDATE_NONTEMPORAL, nt)
-            hip.set_option(hip.OPT_UPDATE_UNROLL, unroll)
+            hip.set_option(hip.OPT_UPDATE_GROUPS, groups)
             dW, dG, dWc, dV = to_dev(W), to_dev(G), to_dev(Wc), to_dev(V)
             hip.easgd_sync_round(dW, dG, dWc, 0.01, 0.1, N=N)
             hip.measgd_round(dW, dV, dG, dWc, 0.01, 0.1, 0.9, N=N)

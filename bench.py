@@ -163,11 +163,21 @@ def triad_ceiling(hip, n=488_000_000, reps=20):
     return 12.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+# HBM bytes per launch of the elastic update measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
+# the reading of the same counter for the triad kernel of known traffic (x2.000 and x1.000); see
+# profiles/elastic_update_cfg4_cfg5_hbm_traffic.md.  Keyed by (momentum, P, N).
+MEASURED_TRAFFIC_BYTES = {
+    (False, 8, 61_000_000): 2_025_422.5 * 1024 * 2.000 + 2_144_537.9 * 1024 * 1.000,
+    (True, 16, 61_000_000): 5_838_007.1 * 1024 * 2.000 + 7_863_305.8 * 1024 * 1.000,
+}
+
+
 def hbm_roofline(wl, update_ms, ceiling_gbs=None):
     achieved = update_bytes(wl) / (update_ms * 1e-3) / 1e9
     out = {"bound": "hbm", "kernel": "elastic_vec4_kernel (measgd)" if wl.momentum else "elastic_vec4_kernel (easgd)",
            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-           "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+           "frac": round(achieved / HBM_PEAK_GBS, 4),
+           "traffic": MEASURED_TRAFFIC_BYTES.get((wl.momentum, wl.P, wl.N)),
            "algorithmic_bytes_per_launch": update_bytes(wl), "avg_launch_ms": round(update_ms, 4)}
     if ceiling_gbs:
         out["measured_triad_ceiling_GBs"] = round(ceiling_gbs, 1)

@@ -103,7 +103,7 @@ int measgd_round(float *W, float *V, const float *G, float *Wc,
  *
  * Requirements: 1 <= n_layers <= 8, every dims[l] >= 1, dims[n_layers] <= 1024,
  * P >= 1, b >= 1, ld >= N, W/G/X 16-byte aligned.  The ReLU derivative at exactly 0 is 0.
- * Errors: EASGD_EINVAL, EASGD_EWORKSPACE, EASGD_ERANGE (an operand above 2^31-1
+ * Errors: EASGD_EINVAL, EASGD_EWORKSPACE, EASGD_ERANGE (an operand above 2^30-1
  * elements per worker), EASGD_ELAUNCH.
  */
 size_t easgd_grad_workspace_bytes(const int *dims, int n_layers, int P, int b);
@@ -124,7 +124,9 @@ size_t easgd_mlp_num_params(const int *dims, int n_layers);
 typedef enum {
     EASGD_OPT_UPDATE_BLOCKS_PER_CU = 1,  /* 0 = one block per tile (default); k>0 = persistent grid of k*CUs blocks */
     EASGD_OPT_UPDATE_NONTEMPORAL   = 2,  /* 1 = streaming (non-temporal) loads/stores for W, G, V (default), 0 = plain */
-    EASGD_OPT_UPDATE_GROUPS        = 3   /* 128-bit groups per thread and worker: 1, 2 or 4 (default); tile = groups*1024 parameters */
+    EASGD_OPT_UPDATE_GROUPS        = 3,  /* 128-bit groups per thread and worker: 1, 2 or 4 (default); tile = groups*1024 parameters */
+    EASGD_OPT_GEMM_TILE            = 4   /* block tile of the wide matrix products of easgd_grad: 0 = chosen per product (default),
+                                            1 = 128x128, 2 = 64x64, 3 = 128x64 */
 } easgd_option;
 
 int easgd_set_option(int option, long value);

@@ -21,6 +21,7 @@ EASGD_OK = 0
 OPT_UPDATE_BLOCKS_PER_CU = 1
 OPT_UPDATE_NONTEMPORAL = 2
 OPT_UPDATE_GROUPS = 3
+OPT_GEMM_TILE = 4
 
 
 class EasgdError(RuntimeError):

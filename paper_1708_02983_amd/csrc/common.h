@@ -22,6 +22,7 @@ struct Options {
     long update_blocks_per_cu = 0;
     long update_nontemporal = 1;
     long update_groups = 4;
+    long gemm_tile = 0;
 };
 Options &options();
 

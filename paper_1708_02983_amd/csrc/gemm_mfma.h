@@ -63,7 +63,7 @@ __device__ __forceinline__ f32x4 fetch4(const float *row, int idx0, int lim, int
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmArgs p)
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(GemmArgs p)
 {
     constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -103,20 +103,28 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
     // chunk c = tid + it*NTHREADS is four consecutive elements along the operand's contiguous axis
     const float *a_src[IT_A], *b_src[IT_B];   // source of the chunk in the slab that starts at k = 0
     int a_dst[IT_A], b_dst[IT_B];             // LDS offset of the chunk's first element
-    bool a_ok[IT_A], b_ok[IT_B];              // false: the row lies outside the matrix, store zeros
+    bool a_ok[IT_A], b_ok[IT_B];              // false: the chunk lies outside the stored matrix (its address was
+                                              // clamped); zeros are stored instead, or 1 in lane a_one[it]
+    int a_one[IT_A];
+    int a_krel[IT_A], b_krel[IT_B];           // k of the chunk's first element relative to the slab start
 #pragma unroll
     for (int it = 0; it < IT_A; ++it) {
         const int c = tid + it * NTHREADS;
         if (A_LAYOUT == K_CONTIG) {
             const int kq = c % (BK / 4), m = c / (BK / 4);
             a_ok[it] = (m0 + m < p.M);
+            a_one[it] = -1;
             a_src[it] = A + (size_t)min(m0 + m, p.M - 1) * p.lda + 4 * kq;
             a_dst[it] = 4 * kq * PITCH_A + m;
+            a_krel[it] = 4 * kq;
         } else {
-            const int mq = c % (BM / 4), k = c / (BM / 4);
-            a_ok[it] = true;
-            a_src[it] = A + (size_t)k * p.lda + m0 + 4 * mq;
+            // with 128-bit loads a_lim is a multiple of 4, so a chunk is entirely inside or entirely outside
+            const int mq = c % (BM / 4), k = c / (BM / 4), m = m0 + 4 * mq;
+            a_ok[it] = (m + 3 < p.a_lim);
+            a_one[it] = (p.a_ones >= m && p.a_ones < m + 4) ? p.a_ones - m : -1;
+            a_src[it] = A + (size_t)k * p.lda + (a_ok[it] ? m : 0);
             a_dst[it] = k * PITCH_A + 4 * mq;
+            a_krel[it] = k;
         }
     }
 #pragma unroll
@@ -127,17 +135,19 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
             b_ok[it] = (n0 + n < p.N);
             b_src[it] = B + (size_t)min(n0 + n, p.N - 1) * p.ldb + 4 * kq;
             b_dst[it] = 4 * kq * PITCH_B + n;
+            b_krel[it] = 4 * kq;
         } else {
-            const int nq = c % (BN / 4), k = c / (BN / 4);
-            b_ok[it] = true;
-            b_src[it] = B + (size_t)k * p.ldb + n0 + 4 * nq;
+            const int nq = c % (BN / 4), k = c / (BN / 4), n = n0 + 4 * nq;
+            b_ok[it] = (n + 3 < b_lim);
+            b_src[it] = B + (size_t)k * p.ldb + (b_ok[it] ? n : 0);
             b_dst[it] = k * PITCH_B + 4 * nq;
+            b_krel[it] = k;
         }
     }
     const size_t a_kstep = (A_LAYOUT == K_CONTIG) ? 1 : (size_t)p.lda;   // address step per unit of k
     const size_t b_kstep = (B_LAYOUT == K_CONTIG) ? 1 : (size_t)p.ldb;
 
-    // Interior slabs: plain 128-bit loads, no lane diverges (rows outside the matrix were clamped above).
+    // Interior slabs: plain 128-bit loads, no lane diverges (chunks outside the matrix were clamped above).
     auto load_fast = [&](int k0, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
 #pragma unroll
         for (int it = 0; it < IT_A; ++it)
@@ -147,6 +157,46 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
         for (int it = 0; it < IT_B; ++it)
             if (CHUNKS_B % NTHREADS == 0 || tid + it * NTHREADS < CHUNKS_B)
                 rb[it] = *reinterpret_cast<const f32x4 *>(b_src[it] + (size_t)k0 * b_kstep);
+    };
+    // The last slab of the K range when it is only partly inside the operands (128-bit path): a chunk is
+    // either entirely inside or entirely outside along k (all limits are multiples of 4), so chunks outside
+    // are loaded from a clamped, valid address and replaced when they are stored to LDS: by zeros, or by
+    // the 1 of the ones vector.
+    const int a_klim = min(p.a_lim, k_end);   // K_CONTIG A: elements at k >= a_klim are not stored
+    const int b_klim = min(b_lim, k_end);
+    bool ta_ok[IT_A], tb_ok[IT_B];
+    auto load_tail = [&](int k0, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
+#pragma unroll
+        for (int it = 0; it < IT_A; ++it) {
+            if (CHUNKS_A % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_A) continue;
+            ta_ok[it] = (A_LAYOUT == K_CONTIG) ? (k0 + a_krel[it] + 3 < a_klim) : (k0 + a_krel[it] < k_end);
+            const int k_eff = ta_ok[it] ? k0 : ((A_LAYOUT == K_CONTIG) ? -a_krel[it] : k0 - a_krel[it]);
+            ra[it] = *reinterpret_cast<const f32x4 *>(a_src[it] + (ptrdiff_t)k_eff * (ptrdiff_t)a_kstep);
+        }
+#pragma unroll
+        for (int it = 0; it < IT_B; ++it) {
+            if (CHUNKS_B % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_B) continue;
+            tb_ok[it] = (B_LAYOUT == K_CONTIG) ? (k0 + b_krel[it] + 3 < b_klim) : (k0 + b_krel[it] < k_end);
+            const int k_eff = tb_ok[it] ? k0 : ((B_LAYOUT == K_CONTIG) ? -b_krel[it] : k0 - b_krel[it]);
+            rb[it] = *reinterpret_cast<const f32x4 *>(b_src[it] + (ptrdiff_t)k_eff * (ptrdiff_t)b_kstep);
+        }
+    };
+    // replaces the chunks of the tail slab that lie outside along k (called on the registers before store_lds)
+    auto fix_tail = [&](int k0, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
+#pragma unroll
+        for (int it = 0; it < IT_A; ++it) {
+            if (CHUNKS_A % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_A) continue;
+            if (!ta_ok[it]) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    ra[it][q] = (A_LAYOUT == K_CONTIG && k0 + a_krel[it] + q == p.a_ones && p.a_ones < k_end) ? 1.f : 0.f;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT_B; ++it) {
+            if (CHUNKS_B % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_B) continue;
+            if (!tb_ok[it]) rb[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
     };
     // Edge slabs and edge tiles: every element guarded (zero fill, ones vector).
     auto load_guarded = [&](int k0, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
@@ -176,16 +226,20 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
         }
     };
 
-    auto store_lds = [&](int buf, const f32x4 (&ra)[IT_A], const f32x4 (&rb)[IT_B], bool zero_rows) {
+    auto store_lds = [&](int buf, const f32x4 (&ra)[IT_A], const f32x4 (&rb)[IT_B], bool clamped) {
 #pragma unroll
         for (int it = 0; it < IT_A; ++it) {
             if (CHUNKS_A % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_A) continue;
             f32x4 v = ra[it];
             if (A_LAYOUT == K_CONTIG) {
-                if (zero_rows && !a_ok[it]) v = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (clamped && !a_ok[it]) v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) As[buf][a_dst[it] + q * PITCH_A] = v[q];
             } else {
+                if (clamped && !a_ok[it]) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = (q == a_one[it]) ? 1.f : 0.f;
+                }
                 *reinterpret_cast<f32x4 *>(&As[buf][a_dst[it]]) = v;
             }
         }
@@ -194,10 +248,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
             if (CHUNKS_B % NTHREADS != 0 && tid + it * NTHREADS >= CHUNKS_B) continue;
             f32x4 v = rb[it];
             if (B_LAYOUT == K_CONTIG) {
-                if (zero_rows && !b_ok[it]) v = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (clamped && !b_ok[it]) v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) Bs[buf][b_dst[it] + q * PITCH_B] = v[q];
             } else {
+                if (clamped && !b_ok[it]) v = f32x4{0.f, 0.f, 0.f, 0.f};
                 *reinterpret_cast<f32x4 *>(&Bs[buf][b_dst[it]]) = v;
             }
         }
@@ -214,7 +269,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
     // MFMA operand fetch: lane l supplies A[m = l%32][k = l/32] and B[k = l/32][n = l%32]
     const int frag_k = lane >> 5, frag_x = lane & 31;
     // multiply the slab held in LDS buffer `buf`; k_left = number of valid k in it
-    auto multiply_slab = [&](int buf, int k_left) {
+    // `mid` runs after half of the full slab's MFMAs have been issued (used to move the next slab registers -> LDS
+    // while the matrix pipeline is busy)
+    auto multiply_slab = [&](int buf, int k_left, auto &&mid) {
         const float *as = &As[buf][frag_k * PITCH_A + wm0 + frag_x];
         const float *bs = &Bs[buf][frag_k * PITCH_B + wn0 + frag_x];
         auto fetch = [&](int kk, float (&a)[TM], float (&b)[TN]) {
@@ -231,17 +288,24 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         };
         if (k_left >= BK) {
-            // operands of k pair kk+2 are fetched from LDS before the MFMAs of pair kk are issued,
-            // so the LDS latency hides behind the matrix pipeline
-            float a[2][TM], b[2][TN];
-            fetch(0, a[0], b[0]);
+            // operands are fetched from LDS DIST k pairs ahead of the MFMAs that use them, so the LDS
+            // latency hides behind the matrix pipeline (one pair ahead = 4 MFMAs when a wave owns 2x2
+            // tiles; two pairs ahead when it owns a single tile)
+            constexpr int DIST = (TM * TN == 1) ? 2 : 1;
+            constexpr int STEPS = BK / 2;
+            float a[DIST + 1][TM], b[DIST + 1][TN];
 #pragma unroll
-            for (int kk = 0; kk < BK; kk += 2) {
-                const int cur = (kk >> 1) & 1;
-                if (kk + 2 < BK) fetch(kk + 2, a[cur ^ 1], b[cur ^ 1]);
+            for (int d = 0; d < DIST; ++d) fetch(2 * d, a[d], b[d]);
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) {
+                if (st + DIST < STEPS) fetch(2 * (st + DIST), a[(st + DIST) % (DIST + 1)], b[(st + DIST) % (DIST + 1)]);
                 __builtin_amdgcn_sched_barrier(0);      // keep the LDS reads ahead of the MFMAs below
-                multiply(a[cur], b[cur]);
+                multiply(a[st % (DIST + 1)], b[st % (DIST + 1)]);
                 __builtin_amdgcn_sched_barrier(0);
+                if (st == STEPS / 2 - 1) {
+                    mid();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         } else {
             // short slab: stop at the last k pair that holds data (the rest of the slab is zero)
@@ -250,85 +314,131 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(GemmAr
                 fetch(kk, a, b);
                 multiply(a, b);
             }
+            mid();
         }
     };
+    auto nothing = [] {};
 
-    // Leading slabs that lie fully inside the stored extent of both operands (decided per block).
+    // All slabs of a block go through the 128-bit pipeline when the operands allow 128-bit loads; the
+    // last slab may be partial (n_full counts the slabs that lie fully inside both operands along k).
     const int n_slabs = (k_end - k_begin + BK - 1) / BK;
-    int n_fast = 0;
+    int n_full = 0, n_pipe = 0;
     {
-        const bool tile_ok = VEC && (A_LAYOUT == K_CONTIG || m0 + BM <= p.a_lim) && (B_LAYOUT == K_CONTIG || n0 + BN <= b_lim);
+        // 128-bit loads need the limits along the contiguous axes to be multiples of 4 (the host only sets VEC then)
+        const bool vec_ok = VEC && (p.a_lim & 3) == 0 && (b_lim & 3) == 0 &&
+                            (A_LAYOUT != K_CONTIG || (a_klim & 3) == 0) && (B_LAYOUT != K_CONTIG || (b_klim & 3) == 0);
         int k_lim = k_end;
-        if (A_LAYOUT == K_CONTIG) k_lim = min(k_lim, p.a_lim);
-        if (B_LAYOUT == K_CONTIG) k_lim = min(k_lim, b_lim);
-        if (tile_ok && k_lim > k_begin) n_fast = (k_lim - k_begin) / BK;
+        if (A_LAYOUT == K_CONTIG) k_lim = min(k_lim, a_klim);
+        if (B_LAYOUT == K_CONTIG) k_lim = min(k_lim, b_klim);
+        if (vec_ok) {
+            n_pipe = n_slabs;
+            n_full = k_lim > k_begin ? (k_lim - k_begin) / BK : 0;
+        }
     }
+    auto load_slab = [&](int s, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
+        if (s < n_full) load_fast(k_begin + s * BK, ra, rb);
+        else load_tail(k_begin + s * BK, ra, rb);
+    };
+    auto store_slab = [&](int buf, int s, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
+        if (s >= n_full) fix_tail(k_begin + s * BK, ra, rb);
+        store_lds(buf, ra, rb, true);
+    };
+    auto k_in_slab = [&](int s) { return min(BK, k_end - (k_begin + s * BK)); };
 
     // Two register stages R0/R1 and two LDS buffers: slab s sits in stage s%2 while in flight and in LDS
     // buffer s%2 while it is multiplied.  In the steady state the loads of slab s+2 are issued, slab s is
-    // multiplied, then slab s+1 moves registers -> LDS: a prefetch distance of two slabs, one barrier per slab.
+    // multiplied and, half way through its MFMAs, slab s+1 moves registers -> LDS: a prefetch distance of two slabs,
+    // one barrier per slab.
     f32x4 ra0[IT_A], rb0[IT_B], ra1[IT_A], rb1[IT_B];
     int s_done = 0;
-    if (n_fast >= 2) {
-        load_fast(k_begin, ra0, rb0);
-        load_fast(k_begin + BK, ra1, rb1);
-        store_lds(0, ra0, rb0, true);
+    if (n_pipe >= 2) {
+        load_slab(0, ra0, rb0);
+        load_slab(1, ra1, rb1);
+        store_slab(0, 0, ra0, rb0);
         __syncthreads();
         int s = 0;
-        for (; s + 3 < n_fast; s += 2) {
-            load_fast(k_begin + (s + 2) * BK, ra0, rb0);
-            multiply_slab(0, BK);
-            store_lds(1, ra1, rb1, true);
+        for (; s + 3 < n_pipe; s += 2) {
+            load_slab(s + 2, ra0, rb0);
+            multiply_slab(0, BK, [&] { store_slab(1, s + 1, ra1, rb1); });
             __syncthreads();
-            load_fast(k_begin + (s + 3) * BK, ra1, rb1);
-            multiply_slab(1, BK);
-            store_lds(0, ra0, rb0, true);
+            load_slab(s + 3, ra1, rb1);
+            multiply_slab(1, BK, [&] { store_slab(0, s + 2, ra0, rb0); });
             __syncthreads();
         }
-        // two or three slabs are left: s (in LDS 0), s+1 (in R1), and s+2 if n_fast is odd
-        const bool three = (s + 2 < n_fast);
-        if (three) load_fast(k_begin + (s + 2) * BK, ra0, rb0);
-        multiply_slab(0, BK);
-        store_lds(1, ra1, rb1, true);
+        // two or three slabs are left: s (in LDS 0), s+1 (in R1), and s+2 if n_pipe is odd
+        const bool three = (s + 2 < n_pipe);
+        if (three) load_slab(s + 2, ra0, rb0);
+        multiply_slab(0, BK, [&] { store_slab(1, s + 1, ra1, rb1); });
         __syncthreads();
-        multiply_slab(1, BK);
         if (three) {
-            store_lds(0, ra0, rb0, true);
+            multiply_slab(1, BK, [&] { store_slab(0, s + 2, ra0, rb0); });
             __syncthreads();
-            multiply_slab(0, BK);
+            multiply_slab(0, k_in_slab(s + 2), nothing);
+        } else {
+            multiply_slab(1, k_in_slab(s + 1), nothing);
         }
         __syncthreads();
-        s_done = n_fast;
+        s_done = n_pipe;
     }
-    // Remaining slabs (edge of K, edge tiles, unaligned operands): load, store, multiply, one at a time.
+    // Otherwise (operands that do not allow 128-bit loads, or a single slab): load, store, multiply, one at a time.
     for (int s = s_done; s < n_slabs; ++s) {
         const int k0 = k_begin + s * BK;
         load_guarded(k0, ra0, rb0);
         store_lds(0, ra0, rb0, false);
         __syncthreads();
-        multiply_slab(0, k_end - k0);
+        multiply_slab(0, k_end - k0, nothing);
         __syncthreads();
     }
 
-    // epilogue: accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
+    // epilogue: accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
+    // Addresses are split into a block-uniform row pointer (scalar arithmetic) and one 32-bit lane offset
+    // that is computed once; tiles that lie fully inside C skip the per-element bounds checks.
     float *__restrict__ C = p.C + (size_t)w * p.c_ws + (size_t)split * p.c_ss;
     const float *__restrict__ mask = (EPI == EPI_MASK) ? p.mask + (size_t)w * p.mask_ws : nullptr;
+    const int wave_m = __builtin_amdgcn_readfirstlane(m0 + wm0), wave_n = __builtin_amdgcn_readfirstlane(n0 + wn0);
+    const unsigned lane_c = (unsigned)(4 * frag_k) * (unsigned)p.ldc + (unsigned)frag_x;
+    const unsigned lane_mask = (unsigned)(4 * frag_k) * (unsigned)p.ldmask + (unsigned)frag_x;
+    if (m0 + BM <= p.M && n0 + BN <= p.N) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + wn0 + j * 32 + frag_x;
+            for (int j = 0; j < TN; ++j) {
+                const int n = wave_n + j * 32;                                        // uniform
+                float gate[16];
+                if (EPI == EPI_MASK) {      // all mask loads of the tile first, so that they overlap
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * frag_k + (r % 4);
-                if (m < p.M && n < p.N) {
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = wave_m + i * 32 + 8 * (r / 4) + (r % 4);
+                        gate[r] = (mask + (size_t)m * p.ldmask + n)[lane_mask];
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = wave_m + i * 32 + 8 * (r / 4) + (r % 4);            // uniform
                     float v = acc[i][j][r];
                     if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
-                    if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
-                    C[(size_t)m * p.ldc + n] = v;
+                    if (EPI == EPI_MASK) v = (gate[r] > 0.f) ? v : 0.f;
+                    (C + (size_t)m * p.ldc + n)[lane_c] = v;
                 }
             }
-        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn0 + j * 32 + frag_x;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * frag_k + (r % 4);
+                    if (m < p.M && n < p.N) {
+                        float v = acc[i][j][r];
+                        if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
+                        if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
+                        C[(size_t)m * p.ldc + n] = v;
+                    }
+                }
+            }
+    }
 }
 
 }  // namespace easgd

@@ -158,8 +158,11 @@ static void launch_gemm(const GemmArgs &a, bool vec, hipStream_t s)
         return;
     }
     const size_t big = (size_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.splits * a.P;
-    if (big >= (size_t)(2 * num_cus())) launch_tile<128, 128, 16, 2, 2, AL, BL, EPI>(a, vec, s);
-    else launch_tile<64, 64, 32, 2, 2, AL, BL, EPI>(a, vec, s);
+    long tile = options().gemm_tile;
+    if (tile == 0) tile = (big >= (size_t)(2 * num_cus())) ? 1 : 2;
+    if (tile == 1) launch_tile<128, 128, 16, 2, 2, AL, BL, EPI>(a, vec, s);
+    else if (tile == 2) launch_tile<64, 64, 32, 2, 2, AL, BL, EPI>(a, vec, s);
+    else launch_tile<128, 64, 32, 2, 2, AL, BL, EPI>(a, vec, s);
 }
 
 static inline bool mult4(size_t x) { return (x & 3u) == 0; }
@@ -198,8 +201,8 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
         return fail(EASGD_EWORKSPACE, "easgd_grad: workspace must be 256-byte aligned and hold %zu bytes (got %zu)", pl.bytes, workspace_bytes);
     for (int l = 0; l < L; ++l) {
         const size_t per_worker = (size_t)(dims[l] + 1) * dims[l + 1];
-        if (per_worker > 0x7fffffffull || (size_t)b * dims[l] > 0x7fffffffull || (size_t)b * dims[l + 1] > 0x7fffffffull)
-            return fail(EASGD_ERANGE, "easgd_grad: layer %d exceeds 2^31-1 elements per worker", l);
+        if (per_worker > 0x3fffffffull || (size_t)b * dims[l] > 0x3fffffffull || (size_t)b * dims[l + 1] > 0x3fffffffull)
+            return fail(EASGD_ERANGE, "easgd_grad: layer %d exceeds 2^30-1 elements per worker", l);
     }
     if ((size_t)P * b * (size_t)pl.splits > 0x7fffffffull) return fail(EASGD_ERANGE, "easgd_grad: P*b too large");
     clear_error();

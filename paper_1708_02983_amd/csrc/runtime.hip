@@ -61,6 +61,10 @@ int easgd_set_option(int option, long value)
         if (value != 1 && value != 2 && value != 4) return easgd::fail(EASGD_EINVAL, "groups must be 1, 2 or 4, got %ld", value);
         o.update_groups = value;
         return EASGD_OK;
+    case EASGD_OPT_GEMM_TILE:
+        if (value < 0 || value > 3) return easgd::fail(EASGD_EINVAL, "gemm tile must be in [0,3], got %ld", value);
+        o.gemm_tile = value;
+        return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
     }
@@ -73,6 +77,7 @@ long easgd_get_option(int option)
     case EASGD_OPT_UPDATE_BLOCKS_PER_CU: return o.update_blocks_per_cu;
     case EASGD_OPT_UPDATE_NONTEMPORAL: return o.update_nontemporal;
     case EASGD_OPT_UPDATE_GROUPS: return o.update_groups;
+    case EASGD_OPT_GEMM_TILE: return o.gemm_tile;
     default: return -1;
     }
 }

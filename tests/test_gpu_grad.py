@@ -108,3 +108,19 @@ def test_full_shape_one_round(hip, name):
         print(f"{name} worker {i}: {flipped} near-zero ReLU gate(s) decided differently in fp32")
         assert abs(loss[i] - loss_ref) <= 1e-5 * abs(loss_ref)
     assert np.isfinite(G[:, :N]).all()
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3])
+def test_every_tile_shape_gives_the_same_gradient(hip, tile):
+    """The block-tile option only changes the launch shape: each forced shape must match the oracle."""
+    dims, P, b = (200, 264, 136, 10), 3, 100
+    N, ld, W, X, y = _problem(dims, P, b)
+    old = hip.get_option(hip.OPT_GEMM_TILE)
+    try:
+        hip.set_option(hip.OPT_GEMM_TILE, tile)
+        G, loss = _run(hip, dims, W, X, y)
+    finally:
+        hip.set_option(hip.OPT_GEMM_TILE, old)
+    for i in range(P):
+        _, loss_ref, _ = match_gradient(G[i], dims, W[i], X[i], y[i], PER_ROUND_TOL)
+        assert abs(loss[i] - loss_ref) <= 1e-5 * abs(loss_ref)

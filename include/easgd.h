@@ -53,8 +53,10 @@ typedef enum {
  *                            W[i][j] <- W[i][j] - eta*(G[i][j] + rho*d_i)        Eq. (1)
  *     Wc[j] <- c + eta*rho * (d_0 + d_1 + ... + d_{P-1})                         Eq. (2)
  *
- * The sum over the workers is taken in ascending i by one thread, so results
- * are bitwise reproducible from run to run and independent of the launch shape.
+ * The sum over the workers is taken in a fixed order (ascending i by one thread;
+ * for small N with P >= 4 the workers are split over four wavefronts whose
+ * partial sums are added in a fixed order), so results are bitwise reproducible
+ * from run to run and independent of the launch-shape options.
  *
  *   W   DEVICE in/out [P][ld]   worker replicas W^i_t -> W^i_{t+1}
  *   G   DEVICE in     [P][ld]   worker gradients dW^i_t (never written)

@@ -142,6 +142,50 @@ __global__ __launch_bounds__(256) void elastic_vec4_kernel(float *__restrict__ W
         elastic_group<MOM, false, 1, float>(Wp, Vp, Gp, Wcp, P, n4 * 4 + threadIdx.x, ld, eta, rho, alpha, delta);
 }
 
+// Small-N path (few parameters, several workers): the one-thread-per-group kernel above would leave most of
+// the chip idle, so the workers are split over the four wavefronts of a block instead.  A block owns 64 groups;
+// wavefront v applies the worker rule for workers v, v+4, v+8, ... (ascending) and keeps a partial sum of
+// W_i - Wc in registers; the partial sums meet in LDS and wavefront 0 adds them in the fixed order
+// v = 0, 1, 2, 3 before it applies Eq. (2).  The result is reproducible from run to run.
+template <bool MOM>
+__global__ __launch_bounds__(256) void elastic_split_kernel(float *__restrict__ Wp, float *__restrict__ Vp,
+                                                            const float *__restrict__ Gp, float *__restrict__ Wcp,
+                                                            int P, size_t N, size_t ld,
+                                                            float eta, float rho, float alpha, float delta)
+{
+    __shared__ f32x4 partial[4][64];
+    f32x4 *__restrict__ W = (f32x4 *)Wp;
+    f32x4 *__restrict__ V = (f32x4 *)Vp;
+    const f32x4 *__restrict__ G = (const f32x4 *)Gp;
+    f32x4 *__restrict__ Wc = (f32x4 *)Wcp;
+    const size_t n4 = N / 4, ld4 = ld / 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t j = (size_t)blockIdx.x * 64 + lane;
+    const bool live = j < n4;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f32x4 c = live ? Wc[j] : zero;
+    f32x4 acc = zero;
+    if (live) {
+        for (int i = wave; i < P; i += 4) {
+            const size_t k = (size_t)i * ld4 + j;
+            f32x4 w = W[k], g = G[k], v = w;
+            if constexpr (MOM) v = V[k];
+            acc += worker_rule<MOM>(w, v, g, c, eta, rho, alpha, delta);
+            W[k] = w;
+            if constexpr (MOM) V[k] = v;
+        }
+    }
+    partial[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && live) {
+        const f32x4 sum = ((partial[0][lane] + partial[1][lane]) + partial[2][lane]) + partial[3][lane];
+        Wc[j] = c + alpha * sum;              // Eq. (2)
+    }
+    const size_t tail = N - n4 * 4;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail)
+        elastic_group<MOM, false, 1, float>(Wp, Vp, Gp, Wcp, P, n4 * 4 + threadIdx.x, ld, eta, rho, alpha, delta);
+}
+
 // Scalar path for operands that are not 16-byte aligned or ld % 4 != 0.
 template <bool MOM>
 __global__ __launch_bounds__(256) void elastic_scalar_kernel(float *__restrict__ W, float *__restrict__ V,
@@ -192,7 +236,12 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
     }
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loop covers the rest
     const dim3 grid((unsigned)blocks);
-    if (vec) {
+    // few parameters and several workers: split the workers over the wavefronts of a block
+    const bool split = vec && P >= 4 && (N / 4 + 255) / 256 < (size_t)(2 * num_cus());
+    if (split) {
+        const dim3 split_grid((unsigned)((N / 4 + 63) / 64 > 0 ? (N / 4 + 63) / 64 : 1));
+        hipLaunchKernelGGL((elastic_split_kernel<MOM>), split_grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    } else if (vec) {
         if (opt.update_nontemporal) launch_vec4<MOM, true>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
         else launch_vec4<MOM, false>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     } else {

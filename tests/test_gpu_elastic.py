@@ -22,8 +22,9 @@ def hip():
     return hip
 
 
-# (P, N, ld): one element, ragged tails (N % 4 = 1, 2, 3), ld > N, several 1024-element tiles
-SHAPES = [(1, 1, 4), (2, 3, 4), (4, 7850, 7852), (3, 4099, 4100), (8, 100_003, 100_004),
+# (P, N, ld): small N with P >= 4 takes the kernel that splits the workers over wavefronts, the others the
+# one-thread-per-group kernel; one element, ragged tails (N % 4 = 1, 2, 3), ld > N, several 1024-element tiles
+SHAPES = [(1, 1, 4), (2, 3, 4), (6, 3, 4), (9, 261, 264), (4, 7850, 7852), (3, 4099, 4100), (8, 100_003, 100_004),
           (16, 33_333, 33_336), (5, 1 << 20, 1 << 20), (32, 65_537, 65_540), (7, 1026, 2048)]
 
 
@@ -111,7 +112,7 @@ def test_hundred_rounds_free_running_and_teacher_forced(hip, momentum):
 
 
 def test_bitwise_reproducible_and_independent_of_launch_shape(hip):
-    P, N = 16, 300_007
+    P, N = 16, 1_200_007        # large enough for the one-thread-per-group kernel, which the options shape
     ld = workloads.round_up(N, 4)
     W, Wc = workloads.update_state(P, N, ld, seed=14)
     G = workloads.update_gradients(P, N, 0, ld, seed=14)

@@ -4,9 +4,12 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1|cfg2|cfg3|cfg4|cfg5]
 
 A step is one whole Sync EASGD round over one batch of synthetic input that is
-already resident in HBM: `easgd_grad` for all P workers followed by the fused
-elastic update (`easgd_sync_round`, or `measgd_round` for momentum workloads);
-for the update-only workloads cfg4/cfg5 a step is the elastic update alone.
+already resident in HBM: one `easgd_mlp_round` call (the gradients of all P
+workers with the elastic update fused into backward propagation).  The same
+rounds are also timed through the two-call path, `easgd_grad` followed by
+`easgd_sync_round` (`measgd_round` for momentum workloads), which isolates the
+matrix-product kernels for the MFMA roofline.  For the update-only workloads
+cfg4/cfg5 a step is the elastic update alone.
 The default workload is cfg2 (MLP 784-1024-1024-10, P=16, b=128); the default
 run also measures the elastic update at AlexNet size (cfg4, cfg5) and reports
 those under "elastic_update" in the same JSON line.
@@ -71,7 +74,7 @@ def _sum_ms(starts, stops):
 # GPU legs
 # ---------------------------------------------------------------------------
 
-def bench_training(hip, wl, steps, warmup):
+def bench_training(hip, wl, steps, warmup, one_call=True):
     import torch
     ld = workloads.round_up(wl.N, 4)
     w0 = workloads.init_packed_weights(wl)
@@ -84,12 +87,18 @@ def bench_training(hip, wl, steps, warmup):
     for t in range(n_batches):
         X, y = workloads.minibatch(wl, t)
         batches.append((torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()))
-    ws = torch.empty(hip.easgd_grad_workspace_bytes(wl.dims, wl.P, wl.batch), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(hip.easgd_mlp_round_workspace_bytes(wl.dims, wl.P, wl.batch), dtype=torch.uint8, device="cuda")
 
     def step(t, ev=None):
         X, y = batches[t % n_batches]
         if ev:
             ev[0].record()
+        if one_call:
+            hip.easgd_mlp_round(wl.dims, dW, dWc, X, y, wl.eta, wl.rho, V=dV, delta=wl.delta or 0.0, workspace=ws)
+            if ev:
+                ev[1].record()
+                ev[2].record()
+            return
         hip.easgd_grad(wl.dims, dW, X, y, dG, None, workspace=ws)
         if ev:
             ev[1].record()
@@ -102,13 +111,19 @@ def bench_training(hip, wl, steps, warmup):
 
     for t in range(warmup):
         step(t)
-    e0, e1, e2 = _events(steps), _events(steps), _events(steps)
+    # the timed region: exactly `steps` rounds, nothing but the library calls between the two synchronisations
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(steps):
-        step(warmup + t, (e0[t], e1[t], e2[t]))
+        step(warmup + t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # a second, instrumented pass over as many rounds gives the duration of each phase from HIP events
+    # (recording events costs some microseconds per round, so it stays out of the timed region)
+    e0, e1, e2 = _events(steps), _events(steps), _events(steps)
+    for t in range(steps):
+        step(warmup + steps + t, (e0[t], e1[t], e2[t]))
+    torch.cuda.synchronize()
     assert bool(torch.isfinite(dWc).all()), "center weights diverged"
     grad_ms = _sum_ms(e0, e1) / steps
     upd_ms = _sum_ms(e1, e2) / steps
@@ -245,6 +260,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--no-extras", action="store_true", help="skip the cfg4/cfg5 elastic-update legs of the default run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--round-overlap", type=int, default=None, choices=(0, 1, 2),
+                    help="library option EASGD_OPT_ROUND_OVERLAP for the one-call path (default: the library's)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P replicas live in one HBM); --gpus must be 1. "
@@ -256,6 +273,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.round_overlap is not None:
+        hip.set_option(hip.OPT_ROUND_OVERLAP, args.round_overlap)
     wl = workloads.WORKLOADS[args.workload]
     steps = args.steps if args.steps is not None else (300 if wl.has_grad else 100)
     warmup = args.warmup if args.warmup is not None else (20 if wl.has_grad else 5)
@@ -266,11 +285,17 @@ def main():
             "config": {"workload": DESCRIPTIONS[args.workload], "P": wl.P, "params_per_replica": wl.N,
                        "eta": wl.eta, "rho": wl.rho, "delta": wl.delta}}
     if wl.has_grad:
-        r = bench_training(hip, wl, steps, warmup)
+        r1 = bench_training(hip, wl, steps, warmup, one_call=True)
+        r = bench_training(hip, wl, steps, warmup, one_call=False)
         tflops = grad_flops(wl) / (r["grad_ms"] * 1e-3) / 1e12
-        line.update({"value": round(steps / r["elapsed_s"], 2), "ms_per_step": round(r["ms_per_step"], 4),
-                     "phases_ms": {"easgd_grad": round(r["grad_ms"], 4), "elastic_update": round(r["update_ms"], 4)}})
-        line["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all products of easgd_grad)",
+        line.update({"value": round(steps / r1["elapsed_s"], 2), "ms_per_step": round(r1["ms_per_step"], 4),
+                     "path": "easgd_mlp_round: one call per round, elastic update fused into backward propagation",
+                     "round_call_ms": round(r1["grad_ms"], 4),
+                     "two_call_path": {"rounds_per_s": round(steps / r["elapsed_s"], 2),
+                                       "ms_per_step": round(r["ms_per_step"], 4),
+                                       "phases_ms": {"easgd_grad": round(r["grad_ms"], 4),
+                                                     "elastic_update": round(r["update_ms"], 4)}}})
+        line["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all products of easgd_grad, two-call path)",
                             "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                             "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
                             "useful_flops_per_launch": grad_flops(wl), "avg_launch_ms": round(r["grad_ms"], 4)}

@@ -8,6 +8,8 @@
  *   steps (2)-(5) easgd_sync_round  broadcast of the center, reduction over the
  *                                   workers, worker rule Eq. (1), center rule Eq. (2)
  *                 measgd_round      the same with the momentum worker rule Eq. (5),(6)
+ *   steps (1)-(5) easgd_mlp_round   the whole round in one call, the update fused into
+ *                                   backward propagation
  *
  * Conventions shared by every entry point
  *   - every pointer marked DEVICE is a device (HBM) pointer owned by the caller;
@@ -116,6 +118,37 @@ int easgd_grad(const int *dims, int n_layers,
                float *G, float *loss,
                void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * A whole Sync EASGD round in one call: steps (1)-(5) of Section 5.1 for the
+ * multilayer perceptron of easgd_grad, with the elastic update fused into
+ * backward propagation (the overlap of steps that Section 5.1 allows).
+ * Eq. (2) runs first and keeps a copy of the time-t center for the rest of
+ * the round; the worker rule Eq. (1) (Eq. (5),(6) when V != NULL) is applied to
+ * layer l's slice of every replica by the kernel that computes that layer's
+ * weight gradient, straight from the accumulators, once no later product of
+ * the round reads W_l.  Every parameter is updated exactly once from time-t values and the
+ * workers are summed in ascending order, so the result equals easgd_grad
+ * followed by easgd_sync_round / measgd_round to rounding.
+ *
+ *   W   DEVICE in/out [P][ld]   replicas W^i_t -> W^i_{t+1}
+ *   V   DEVICE in/out [P][ld]   momentum buffers, or NULL for the plain rule Eq. (1)
+ *   Wc  DEVICE in/out [N]       center weights
+ *   G   DEVICE out    [P][ld]   the gradients dW^i_t of this round, or NULL when the
+ *                               caller does not need them (they are then never stored)
+ *   delta is ignored when V == NULL; the other arguments are those of easgd_grad
+ *   and easgd_sync_round, with the same requirements; the workspace must hold
+ *   easgd_mlp_round_workspace_bytes(...) bytes.
+ * Errors: as easgd_grad.
+ */
+size_t easgd_mlp_round_workspace_bytes(const int *dims, int n_layers, int P, int b);
+
+int easgd_mlp_round(const int *dims, int n_layers,
+                    float *W, float *V, float *Wc, size_t ld,
+                    const float *X, const int32_t *y, int P, int b,
+                    float *G, float *loss,
+                    float eta, float rho, float delta,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 /* Number of parameters N of the packed layout for `dims`; 0 on invalid input. */
 size_t easgd_mlp_num_params(const int *dims, int n_layers);
 
@@ -127,8 +160,12 @@ typedef enum {
     EASGD_OPT_UPDATE_BLOCKS_PER_CU = 1,  /* 0 = one block per tile (default); k>0 = persistent grid of k*CUs blocks */
     EASGD_OPT_UPDATE_NONTEMPORAL   = 2,  /* 1 = streaming (non-temporal) loads/stores for W, G, V (default), 0 = plain */
     EASGD_OPT_UPDATE_GROUPS        = 3,  /* 128-bit groups per thread and worker: 1, 2 or 4 (default); tile = groups*1024 parameters */
-    EASGD_OPT_GEMM_TILE            = 4   /* block tile of the wide matrix products of easgd_grad: 0 = chosen per product (default),
+    EASGD_OPT_GEMM_TILE            = 4,  /* block tile of the wide matrix products of easgd_grad: 0 = chosen per product (default),
                                             1 = 128x128, 2 = 64x64, 3 = 128x64 */
+    EASGD_OPT_ROUND_OVERLAP        = 5   /* easgd_mlp_round: the center rule may run on a second stream of the library, beside
+                                            forward propagation: 0 = never (every kernel on the caller's stream), 1 = when
+                                            P*N >= 2^24, below which ordering the two streams costs more than it hides
+                                            (default), 2 = always */
 } easgd_option;
 
 int easgd_set_option(int option, long value);

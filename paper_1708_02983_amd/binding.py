@@ -22,6 +22,7 @@ OPT_UPDATE_BLOCKS_PER_CU = 1
 OPT_UPDATE_NONTEMPORAL = 2
 OPT_UPDATE_GROUPS = 3
 OPT_GEMM_TILE = 4
+OPT_ROUND_OVERLAP = 5
 
 
 class EasgdError(RuntimeError):
@@ -46,6 +47,10 @@ def _load() -> ctypes.CDLL:
     lib.easgd_grad_workspace_bytes.restype = sz
     lib.easgd_grad.argtypes = [ip, i, vp, sz, vp, vp, i, i, vp, vp, vp, sz, vp]
     lib.easgd_grad.restype = i
+    lib.easgd_mlp_round_workspace_bytes.argtypes = [ip, i, i, i]
+    lib.easgd_mlp_round_workspace_bytes.restype = sz
+    lib.easgd_mlp_round.argtypes = [ip, i, vp, vp, vp, sz, vp, vp, i, i, vp, vp, f, f, f, vp, sz, vp]
+    lib.easgd_mlp_round.restype = i
     lib.easgd_mlp_num_params.argtypes = [ip, i]
     lib.easgd_mlp_num_params.restype = sz
     lib.easgd_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -154,6 +159,44 @@ def easgd_grad(dims: Sequence[int], W, X, y, G, loss=None, workspace=None, strea
                            None if loss is None else _dev("loss", loss, torch.float32, P),
                            _dev("workspace", workspace, torch.uint8, nbytes), workspace.numel(),
                            _stream(stream)))
+    return workspace
+
+
+def easgd_mlp_round_workspace_bytes(dims: Sequence[int], P: int, b: int) -> int:
+    arr, L = _dims(dims)
+    return int(_lib.easgd_mlp_round_workspace_bytes(arr, L, P, b))
+
+
+def easgd_mlp_round(dims: Sequence[int], W, Wc, X, y, eta: float, rho: float, V=None, delta: float = 0.0,
+                    G=None, loss=None, workspace=None, stream=None):
+    """Steps (1)-(5) in one call, the update fused into backward propagation; V selects Eq. (5),(6);
+    the gradients are stored only when G is given.  Returns the workspace used."""
+    arr, L = _dims(dims)
+    if W.dim() != 2 or X.dim() != 3 or y.dim() != 2:
+        raise ValueError("expected W[P][ld], X[P][b][d_in], y[P][b]")
+    P, ld = W.shape
+    b = X.shape[1]
+    N = easgd_mlp_num_params(dims)
+    if N == 0:
+        raise ValueError(f"invalid layer widths {list(dims)}")
+    if X.shape[0] != P or X.shape[2] != dims[0] or tuple(y.shape) != (P, b):
+        raise ValueError("X / y shapes do not match W and dims")
+    if V is not None and tuple(V.shape) != (P, ld):
+        raise ValueError("V must have the shape of W")
+    need = (P - 1) * ld + N
+    nbytes = easgd_mlp_round_workspace_bytes(dims, P, b)
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    _check(_lib.easgd_mlp_round(arr, L, _dev("W", W, torch.float32, need),
+                                None if V is None else _dev("V", V, torch.float32, need),
+                                _dev("Wc", Wc, torch.float32, N), ld,
+                                _dev("X", X, torch.float32, P * b * dims[0]),
+                                _dev("y", y, torch.int32, P * b), P, b,
+                                None if G is None else _dev("G", G, torch.float32, need),
+                                None if loss is None else _dev("loss", loss, torch.float32, P),
+                                eta, rho, delta,
+                                _dev("workspace", workspace, torch.uint8, nbytes), workspace.numel(),
+                                _stream(stream)))
     return workspace
 
 

@@ -23,8 +23,18 @@ struct Options {
     long update_nontemporal = 1;
     long update_groups = 4;
     long gemm_tile = 0;
+    long round_overlap = 1;
 };
 Options &options();
+
+// Steps (2)-(5) of a round on the parameter range [0, N) of every replica (defined with the
+// elastic update kernels); V == nullptr selects Eq. (1), otherwise Eq. (5),(6).
+int elastic_range(float *W, float *V, const float *G, float *Wc, int P, size_t N, size_t ld,
+                  float eta, float rho, float delta, void *stream);
+
+// Eq. (2) alone, ahead of the worker rules: Wc[j] <- Wc[j] + alpha * sum_i (W_i[j] - Wc[j]), ascending i;
+// the time-t center is saved to old[0..N).
+int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t ld, float alpha, void *stream);
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

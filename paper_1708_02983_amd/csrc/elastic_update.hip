@@ -15,6 +15,7 @@
 // on MI355X this is 2-5 % faster than having every thread interleave several
 // workers (HBM efficiency drops as more address streams are active at once).
 #include "common.h"
+#include "elastic_rule.h"
 
 namespace easgd {
 
@@ -32,20 +33,6 @@ __device__ __forceinline__ void stream_store(T *p, T v)
 {
     if constexpr (NT) __builtin_nontemporal_store(v, p);
     else *p = v;
-}
-
-// One worker's rule applied to T = float or f32x4 lanes.  Returns d = w - c.
-template <bool MOM, typename T>
-__device__ __forceinline__ T worker_rule(T &w, T &v, T g, T c, float eta, float rho, float alpha, float delta)
-{
-    const T d = w - c;
-    if constexpr (MOM) {
-        v = delta * v - eta * g;              // Eq. (5)
-        w = (w + v) - alpha * d;              // Eq. (6)
-    } else {
-        w = w - eta * (g + rho * d);          // Eq. (1)
-    }
-    return d;
 }
 
 // T-wide groups [0, n_groups) of every row; rows are `ld_groups` groups apart.
@@ -248,6 +235,64 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
         hipLaunchKernelGGL((elastic_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     }
     return check_launch(name);
+}
+
+// Eq. (2) alone, ahead of the worker rules: Wc[j] <- c + alpha * sum_i (W_i[j] - c) with c = Wc[j], workers in
+// ascending order (the order of the fused kernels above), while the time-t value c is saved to old[j] for the
+// worker rules that run later in the round.  W is read with ordinary loads: the same values are needed again soon.
+template <typename T>
+__global__ __launch_bounds__(256) void center_rule_kernel(const float *__restrict__ Wp, float *__restrict__ Wcp,
+                                                          float *__restrict__ oldp, int P, size_t N, size_t ld, float alpha)
+{
+    constexpr size_t LANES = sizeof(T) / sizeof(float);
+    const T *__restrict__ W = (const T *)Wp;
+    T *__restrict__ Wc = (T *)Wcp;
+    T *__restrict__ old = (T *)oldp;
+    const size_t n = N / LANES, ldt = ld / LANES;
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j < n) {
+        const T c = Wc[j];
+        T acc = c - c;
+        int i = 0;
+        for (; i + 4 <= P; i += 4) {
+            T w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) w[u] = W[(size_t)(i + u) * ldt + j];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc += w[u] - c;
+        }
+        for (; i < P; ++i) acc += W[(size_t)i * ldt + j] - c;
+        old[j] = c;
+        Wc[j] = c + alpha * acc;
+    }
+    const size_t tail = N - n * LANES;        // only for T = f32x4
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail) {
+        const size_t k = n * LANES + threadIdx.x;
+        const float c = Wcp[k];
+        float acc = 0.f;
+        for (int i = 0; i < P; ++i) acc += Wp[(size_t)i * ld + k] - c;
+        oldp[k] = c;
+        Wcp[k] = c + alpha * acc;
+    }
+}
+
+int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t ld, float alpha, void *stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool vec = aligned16(W) && aligned16(Wc) && aligned16(old) && (ld % 4 == 0);
+    const size_t units = vec ? N / 4 : N;
+    const size_t blocks = units / 256 + 1;    // the last block also owns the scalar tail
+    if (blocks > 0x7fffffffu) return fail(EASGD_ERANGE, "center rule: N too large");
+    if (vec) hipLaunchKernelGGL((center_rule_kernel<f32x4>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
+    else hipLaunchKernelGGL((center_rule_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
+    return check_launch("center rule");
+}
+
+int elastic_range(float *W, float *V, const float *G, float *Wc, int P, size_t N, size_t ld,
+                  float eta, float rho, float delta, void *stream)
+{
+    return V ? elastic_round<true>(W, V, G, Wc, P, N, ld, eta, rho, delta, stream)
+             : elastic_round<false>(W, nullptr, G, Wc, P, N, ld, eta, rho, 0.0f, stream);
 }
 
 }  // namespace easgd

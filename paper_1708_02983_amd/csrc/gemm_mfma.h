@@ -21,11 +21,15 @@
 // MFMA operand fetch is one conflict-free ds_read_b32 per lane.
 #pragma once
 #include "common.h"
+#include "elastic_rule.h"
 
 namespace easgd {
 
 enum { K_CONTIG = 0, MN_CONTIG = 1 };
-enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
+// EPI_ELASTIC / EPI_ELASTIC_MOM: the product is a gradient tile g; the epilogue applies the worker rule
+// Eq. (1) / Eq. (5),(6) to the matching tile of the replica (and momentum buffer) in place, with the
+// time-t center read from `center`; g itself is stored only when C is not null.
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_ELASTIC = 3, EPI_ELASTIC_MOM = 4 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -43,6 +47,11 @@ struct GemmArgs {
     int splits;
     int tiles_m, tiles_n;
     int P;
+    // elastic epilogues: replica / momentum tiles indexed like C (worker stride c_ws, row stride ldc);
+    // the center has the row stride ldc and no worker stride
+    float *Wt, *Vt;
+    const float *center;
+    float eta, rho, alpha, delta;
 };
 
 // Four elements idx0..idx0+3 along the contiguous axis of a row that starts at `row`.
@@ -393,8 +402,14 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
     // epilogue: accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
     // Addresses are split into a block-uniform row pointer (scalar arithmetic) and one 32-bit lane offset
     // that is computed once; tiles that lie fully inside C skip the per-element bounds checks.
-    float *__restrict__ C = p.C + (size_t)w * p.c_ws + (size_t)split * p.c_ss;
+    constexpr bool ELASTIC = (EPI == EPI_ELASTIC || EPI == EPI_ELASTIC_MOM);
+    constexpr bool MOM = (EPI == EPI_ELASTIC_MOM);
+    const bool keep = !ELASTIC || p.C != nullptr;                                     // uniform
+    float *__restrict__ C = keep ? p.C + (size_t)w * p.c_ws + (size_t)split * p.c_ss : nullptr;
     const float *__restrict__ mask = (EPI == EPI_MASK) ? p.mask + (size_t)w * p.mask_ws : nullptr;
+    float *__restrict__ Wr = ELASTIC ? p.Wt + (size_t)w * p.c_ws : nullptr;
+    float *__restrict__ Vr = MOM ? p.Vt + (size_t)w * p.c_ws : nullptr;
+    const float *__restrict__ Cc = ELASTIC ? p.center : nullptr;
     const int wave_m = __builtin_amdgcn_readfirstlane(m0 + wm0), wave_n = __builtin_amdgcn_readfirstlane(n0 + wn0);
     const unsigned lane_c = (unsigned)(4 * frag_k) * (unsigned)p.ldc + (unsigned)frag_x;
     const unsigned lane_mask = (unsigned)(4 * frag_k) * (unsigned)p.ldmask + (unsigned)frag_x;
@@ -404,6 +419,26 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = wave_n + j * 32;                                        // uniform
+                if constexpr (ELASTIC) {
+                    float wv[16], cv[16], vv[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {  // all loads of the tile first, so that they overlap
+                        const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
+                        wv[r] = (Wr + row)[lane_c];
+                        cv[r] = (Cc + row)[lane_c];
+                        vv[r] = MOM ? (Vr + row)[lane_c] : 0.f;
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
+                        const float g = acc[i][j][r];
+                        worker_rule<MOM>(wv[r], vv[r], g, cv[r], p.eta, p.rho, p.alpha, p.delta);
+                        (Wr + row)[lane_c] = wv[r];
+                        if (MOM) (Vr + row)[lane_c] = vv[r];
+                        if (keep) (C + row)[lane_c] = g;
+                    }
+                    continue;
+                }
                 float gate[16];
                 if (EPI == EPI_MASK) {      // all mask loads of the tile first, so that they overlap
 #pragma unroll
@@ -432,9 +467,18 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
                     const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * frag_k + (r % 4);
                     if (m < p.M && n < p.N) {
                         float v = acc[i][j][r];
-                        if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
-                        if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
-                        C[(size_t)m * p.ldc + n] = v;
+                        const size_t at = (size_t)m * p.ldc + n;
+                        if constexpr (ELASTIC) {
+                            float wv = Wr[at], vv = MOM ? Vr[at] : 0.f;
+                            worker_rule<MOM>(wv, vv, v, Cc[at], p.eta, p.rho, p.alpha, p.delta);
+                            Wr[at] = wv;
+                            if (MOM) Vr[at] = vv;
+                            if (keep) C[at] = v;
+                        } else {
+                            if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
+                            if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
+                            C[at] = v;
+                        }
                     }
                 }
             }

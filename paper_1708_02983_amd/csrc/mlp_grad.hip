@@ -12,6 +12,7 @@
 // The last layer's logits are produced as split-K partial sums that the softmax
 // kernel adds in ascending split order, so every sum has a fixed order.
 #include "gemm_mfma.h"
+#include <mutex>
 
 namespace easgd {
 
@@ -28,6 +29,7 @@ struct GradPlan {
     size_t logits_off = 0, rowloss_off = 0, dz_off[2] = {0, 0};
     size_t bytes = 0;
     int splits = 1, k_per_split = 0;
+    size_t center_off = 0, round_bytes = 0;
 };
 
 static constexpr int SPLIT_BK = 16;     // slab depth of the kernel that produces the logits
@@ -68,6 +70,8 @@ static bool make_plan(const int *dims, int L, int P, int b, GradPlan &pl)
         o += align_up((size_t)P * b * widest * sizeof(float), 256);
     }
     pl.bytes = o;
+    pl.center_off = o;                   // whole-round call only: the center at time t
+    pl.round_bytes = o + align_up(pl.N * sizeof(float), 256);
     return true;
 }
 
@@ -148,10 +152,12 @@ static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
     else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI>), grid, block, 0, s, a);
 }
 
-// Picks the tile shape: 128x128 when that still gives every CU about two blocks,
-// 64x64 otherwise; outputs at most 32 wide use a 128x32 tile.
+// Picks the tile shape.  Outputs at most 32 wide use a 128x32 tile.  Otherwise 64x64 blocks (four per
+// compute unit, so that the epilogue of one overlaps the products of the others) unless the caller asks
+// for the large tile and it still gives every compute unit about two blocks: that pays for the long-K
+// forward products, not for the short-K weight gradients with their heavy epilogues.
 template <int AL, int BL, int EPI>
-static void launch_gemm(const GemmArgs &a, bool vec, hipStream_t s)
+static void launch_gemm(const GemmArgs &a, bool vec, bool large_ok, hipStream_t s)
 {
     if (a.N <= 32) {
         launch_tile<128, 32, SPLIT_BK, 4, 1, AL, BL, EPI>(a, vec, s);
@@ -159,13 +165,54 @@ static void launch_gemm(const GemmArgs &a, bool vec, hipStream_t s)
     }
     const size_t big = (size_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.splits * a.P;
     long tile = options().gemm_tile;
-    if (tile == 0) tile = (big >= (size_t)(2 * num_cus())) ? 1 : 2;
+    if (tile == 0) tile = (large_ok && big >= (size_t)(2 * num_cus())) ? 1 : 2;
     if (tile == 1) launch_tile<128, 128, 16, 2, 2, AL, BL, EPI>(a, vec, s);
     else if (tile == 2) launch_tile<64, 64, 32, 2, 2, AL, BL, EPI>(a, vec, s);
     else launch_tile<128, 64, 32, 2, 2, AL, BL, EPI>(a, vec, s);
 }
 
 static inline bool mult4(size_t x) { return (x & 3u) == 0; }
+
+// Elastic update fused into the backward pass.  Eq. (2) runs first and saves the time-t
+// center in the workspace for the worker rules; the worker rule is the epilogue of each
+// layer's weight-gradient product, which runs after the layer's input-gradient product, the
+// last reader of W_l at time t.
+struct ElasticStep {
+    float *W, *V, *Wc;
+    float eta, rho, delta;
+};
+
+static int grad_impl(const char *name, const int *dims, int n_layers, const float *W, size_t ld, const float *X,
+                     const int32_t *y, int P, int b, float *G, float *loss, void *workspace, size_t workspace_bytes,
+                     void *stream, const ElasticStep *step);
+
+// A second stream per device (default priority) with the two events that order it against the caller's
+// stream: `fork` is recorded on the caller's stream when the round starts, `join` on the second stream when
+// the center rule is done.  Created on first use and kept until the process ends; whole-round calls hold
+// `side_mutex`, so that two host threads never interleave their record/wait pairs.
+struct SideLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool tried = false, ok = false;
+};
+static std::mutex side_mutex;
+static constexpr int MAX_DEVICES = 64;
+static SideLane side_lanes[MAX_DEVICES];
+
+static SideLane *side_lane()       // call with side_mutex held; nullptr when no lane can be made
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    SideLane &ln = side_lanes[dev];
+    if (!ln.tried) {
+        ln.tried = true;
+        ln.ok = hipStreamCreateWithFlags(&ln.stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&ln.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&ln.join, hipEventDisableTiming) == hipSuccess;
+        if (!ln.ok) (void)hipGetLastError();
+    }
+    return ln.ok ? &ln : nullptr;
+}
 
 }  // namespace easgd
 
@@ -185,26 +232,55 @@ size_t easgd_grad_workspace_bytes(const int *dims, int n_layers, int P, int b)
     return pl.bytes;
 }
 
+size_t easgd_mlp_round_workspace_bytes(const int *dims, int n_layers, int P, int b)
+{
+    easgd::GradPlan pl;
+    if (!easgd::make_plan(dims, n_layers, P, b, pl)) return 0;
+    return pl.round_bytes;
+}
+
 int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const float *X, const int32_t *y,
                int P, int b, float *G, float *loss, void *workspace, size_t workspace_bytes, void *stream)
 {
-    using namespace easgd;
+    return easgd::grad_impl("easgd_grad", dims, n_layers, W, ld, X, y, P, b, G, loss, workspace, workspace_bytes,
+                            stream, nullptr);
+}
+
+int easgd_mlp_round(const int *dims, int n_layers, float *W, float *V, float *Wc, size_t ld,
+                    const float *X, const int32_t *y, int P, int b, float *G, float *loss,
+                    float eta, float rho, float delta, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Wc) return easgd::fail(EASGD_EINVAL, "easgd_mlp_round: NULL pointer");
+    const easgd::ElasticStep step = {W, V, Wc, eta, rho, delta};
+    return easgd::grad_impl("easgd_mlp_round", dims, n_layers, W, ld, X, y, P, b, G, loss, workspace,
+                            workspace_bytes, stream, &step);
+}
+
+}  // extern "C"
+
+namespace easgd {
+
+static int grad_impl(const char *name, const int *dims, int n_layers, const float *W, size_t ld, const float *X,
+                     const int32_t *y, int P, int b, float *G, float *loss, void *workspace, size_t workspace_bytes,
+                     void *stream, const ElasticStep *step)
+{
     const int L = n_layers;
     GradPlan pl;
-    if (!W || !X || !y || !G) return fail(EASGD_EINVAL, "easgd_grad: NULL pointer");
+    if (!W || !X || !y || (!G && !step)) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
     if (!make_plan(dims, L, P, b, pl))
-        return fail(EASGD_EINVAL, "easgd_grad: need 1 <= n_layers <= %d, all dims >= 1, P >= 1, b >= 1", MAX_LAYERS);
-    if (dims[L] > MAX_CLASSES) return fail(EASGD_EINVAL, "easgd_grad: at most %d classes, got %d", MAX_CLASSES, dims[L]);
-    if (ld < pl.N) return fail(EASGD_EINVAL, "easgd_grad: ld (%zu) < N (%zu)", ld, pl.N);
-    if (!aligned16(W) || !aligned16(G) || !aligned16(X)) return fail(EASGD_EINVAL, "easgd_grad: W, G, X must be 16-byte aligned");
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < pl.bytes)
-        return fail(EASGD_EWORKSPACE, "easgd_grad: workspace must be 256-byte aligned and hold %zu bytes (got %zu)", pl.bytes, workspace_bytes);
+        return fail(EASGD_EINVAL, "%s: need 1 <= n_layers <= %d, all dims >= 1, P >= 1, b >= 1", name, MAX_LAYERS);
+    if (dims[L] > MAX_CLASSES) return fail(EASGD_EINVAL, "%s: at most %d classes, got %d", name, MAX_CLASSES, dims[L]);
+    if (ld < pl.N) return fail(EASGD_EINVAL, "%s: ld (%zu) < N (%zu)", name, ld, pl.N);
+    if (!aligned16(W) || !aligned16(G) || !aligned16(X)) return fail(EASGD_EINVAL, "%s: W, G, X must be 16-byte aligned", name);
+    const size_t need_bytes = step ? pl.round_bytes : pl.bytes;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need_bytes)
+        return fail(EASGD_EWORKSPACE, "%s: workspace must be 256-byte aligned and hold %zu bytes (got %zu)", name, need_bytes, workspace_bytes);
     for (int l = 0; l < L; ++l) {
         const size_t per_worker = (size_t)(dims[l] + 1) * dims[l + 1];
         if (per_worker > 0x3fffffffull || (size_t)b * dims[l] > 0x3fffffffull || (size_t)b * dims[l + 1] > 0x3fffffffull)
-            return fail(EASGD_ERANGE, "easgd_grad: layer %d exceeds 2^30-1 elements per worker", l);
+            return fail(EASGD_ERANGE, "%s: layer %d exceeds 2^30-1 elements per worker", name, l);
     }
-    if ((size_t)P * b * (size_t)pl.splits > 0x7fffffffull) return fail(EASGD_ERANGE, "easgd_grad: P*b too large");
+    if ((size_t)P * b * (size_t)pl.splits > 0x7fffffffull) return fail(EASGD_ERANGE, "%s: P*b too large", name);
     clear_error();
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -213,6 +289,32 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
     float *logits = reinterpret_cast<float *>(ws + pl.logits_off);
     float *dz[2] = {reinterpret_cast<float *>(ws + pl.dz_off[0]), reinterpret_cast<float *>(ws + pl.dz_off[1])};
     const bool base_vec = mult4(ld);
+
+    // ---- Eq. (2); beside forward propagation when the second stream is in use ----
+    float *old_center = step ? reinterpret_cast<float *>(ws + pl.center_off) : nullptr;
+    std::unique_lock<std::mutex> lane_guard;
+    SideLane *lane = nullptr;
+    if (step) {
+        // ordering two streams against each other costs some tens of microseconds of latency: by default the
+        // second stream is used only when the center rule has enough to read to be worth hiding
+        const long overlap = options().round_overlap;
+        if (overlap == 2 || (overlap == 1 && (size_t)P * pl.N >= ((size_t)1 << 24))) {
+            lane_guard = std::unique_lock<std::mutex>(side_mutex);
+            lane = side_lane();
+        }
+        const float alpha = step->eta * step->rho;
+        int rc;
+        if (lane) {
+            if (hipEventRecord(lane->fork, s) != hipSuccess || hipStreamWaitEvent(lane->stream, lane->fork, 0) != hipSuccess)
+                return check_launch(name) != EASGD_OK ? EASGD_ELAUNCH : fail(EASGD_ELAUNCH, "%s: stream fork failed", name);
+            rc = center_range(step->W, step->Wc, old_center, P, pl.N, ld, alpha, lane->stream);
+            if (rc == EASGD_OK && hipEventRecord(lane->join, lane->stream) != hipSuccess)
+                rc = fail(EASGD_ELAUNCH, "%s: stream join failed", name);
+        } else {
+            rc = center_range(step->W, step->Wc, old_center, P, pl.N, ld, alpha, s);
+        }
+        if (rc != EASGD_OK) return rc;
+    }
 
     // ---- forward propagation ----
     for (int l = 0; l < L; ++l) {
@@ -227,8 +329,8 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
         a.k_per_split = last ? pl.k_per_split : ((a.K + 63) / 64 * 64);
         a.c_ss = (size_t)P * b * d_out;
         const bool vec = base_vec && mult4(d_in) && mult4(d_out) && mult4(pl.off[l]);
-        if (last) launch_gemm<K_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, s);
-        else launch_gemm<K_CONTIG, MN_CONTIG, EPI_RELU>(a, vec, s);
+        if (last) launch_gemm<K_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, true, s);
+        else launch_gemm<K_CONTIG, MN_CONTIG, EPI_RELU>(a, vec, true, s);
     }
     float *row_loss = reinterpret_cast<float *>(ws + pl.rowloss_off);
     const int rows = P * b;
@@ -240,15 +342,6 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
     for (int l = L - 1; l >= 0; --l) {
         const int d_in = dims[l], d_out = dims[l + 1];
         const float *dz_l = dz[l & 1];
-        {   // [dW_l ; db_l] = [A_l 1]^T dZ_l, stored at the layer's place in the packed gradient
-            GemmArgs a = {};
-            a.A = act(l); a.a_ws = (size_t)b * d_in; a.lda = d_in; a.a_lim = d_in; a.a_ones = d_in;
-            a.B = dz_l; a.b_ws = (size_t)b * d_out; a.ldb = d_out;
-            a.C = G + pl.off[l]; a.c_ws = ld; a.ldc = d_out;
-            a.M = d_in + 1; a.N = d_out; a.K = b; a.P = P;
-            a.splits = 1; a.k_per_split = (a.K + 63) / 64 * 64;
-            launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(a, mult4(d_in) && mult4(d_out), s);
-        }
         if (l > 0) {   // dZ_{l-1} = (dZ_l W_l^T) where A_l > 0
             GemmArgs a = {};
             a.A = dz_l; a.a_ws = (size_t)b * d_out; a.lda = d_out; a.a_lim = d_out; a.a_ones = -1;
@@ -257,10 +350,32 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
             a.mask = act(l); a.mask_ws = (size_t)b * d_in; a.ldmask = d_in;
             a.M = b; a.N = d_in; a.K = d_out; a.P = P;
             a.splits = 1; a.k_per_split = (a.K + 63) / 64 * 64;
-            launch_gemm<K_CONTIG, K_CONTIG, EPI_MASK>(a, base_vec && mult4(d_out) && mult4(pl.off[l]), s);
+            launch_gemm<K_CONTIG, K_CONTIG, EPI_MASK>(a, base_vec && mult4(d_out) && mult4(pl.off[l]), false, s);
+        }
+        {   // [dW_l ; db_l] = [A_l 1]^T dZ_l, stored at the layer's place in the packed gradient
+            GemmArgs a = {};
+            a.A = act(l); a.a_ws = (size_t)b * d_in; a.lda = d_in; a.a_lim = d_in; a.a_ones = d_in;
+            a.B = dz_l; a.b_ws = (size_t)b * d_out; a.ldb = d_out;
+            a.C = G ? G + pl.off[l] : nullptr; a.c_ws = ld; a.ldc = d_out;
+            a.M = d_in + 1; a.N = d_out; a.K = b; a.P = P;
+            a.splits = 1; a.k_per_split = (a.K + 63) / 64 * 64;
+            const bool vec = mult4(d_in) && mult4(d_out);
+            if (!step) {
+                launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, false, s);
+            } else {
+                // the first kernel that changes W waits for the center rule, which reads W at time t
+                if (lane && l == L - 1 && hipStreamWaitEvent(s, lane->join, 0) != hipSuccess)
+                    return fail(EASGD_ELAUNCH, "%s: stream join failed", name);
+                a.Wt = step->W + pl.off[l];
+                a.Vt = step->V ? step->V + pl.off[l] : nullptr;
+                a.center = old_center + pl.off[l];
+                a.eta = step->eta; a.rho = step->rho; a.alpha = step->eta * step->rho; a.delta = step->delta;
+                if (step->V) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM>(a, vec, false, s);
+                else launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC>(a, vec, false, s);
+            }
         }
     }
-    return check_launch("easgd_grad");
+    return check_launch(name);
 }
 
-}  // extern "C"
+}  // namespace easgd

@@ -65,6 +65,10 @@ int easgd_set_option(int option, long value)
         if (value < 0 || value > 3) return easgd::fail(EASGD_EINVAL, "gemm tile must be in [0,3], got %ld", value);
         o.gemm_tile = value;
         return EASGD_OK;
+    case EASGD_OPT_ROUND_OVERLAP:
+        if (value < 0 || value > 2) return easgd::fail(EASGD_EINVAL, "round overlap must be 0, 1 or 2, got %ld", value);
+        o.round_overlap = value;
+        return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
     }
@@ -78,6 +82,7 @@ long easgd_get_option(int option)
     case EASGD_OPT_UPDATE_NONTEMPORAL: return o.update_nontemporal;
     case EASGD_OPT_UPDATE_GROUPS: return o.update_groups;
     case EASGD_OPT_GEMM_TILE: return o.gemm_tile;
+    case EASGD_OPT_ROUND_OVERLAP: return o.round_overlap;
     default: return -1;
     }
 }

@@ -40,9 +40,14 @@ def test_num_params_and_workspace(lib):
         assert lib.easgd_mlp_num_params(arr, len(dims) - 1) == n
         ws = lib.easgd_grad_workspace_bytes(arr, len(dims) - 1, 4, 64)
         assert ws > 0 and ws % 256 == 0
+        # the whole-round call also keeps the new center (N floats) in the workspace
+        lib.easgd_mlp_round_workspace_bytes.restype = ctypes.c_size_t
+        wr = lib.easgd_mlp_round_workspace_bytes(arr, len(dims) - 1, 4, 64)
+        assert wr % 256 == 0 and 4 * n <= wr - ws < 4 * n + 256
     bad = (ctypes.c_int * 2)(784, 0)
     assert lib.easgd_mlp_num_params(bad, 1) == 0
     assert lib.easgd_grad_workspace_bytes(bad, 1, 4, 64) == 0
+    assert lib.easgd_mlp_round_workspace_bytes(bad, 1, 4, 64) == 0
 
 
 def test_bad_arguments_are_rejected_without_a_launch(lib):
@@ -66,6 +71,15 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert lib.easgd_grad(dims, 0, fake, 7850, fake, fake, 1, 1, fake, None, fake, 1 << 30, None) == -1
     assert lib.easgd_grad(dims, 1, fake, 7850, fake, fake, 1, 1, fake, None, None, 0, None) == -3          # workspace
     assert lib.easgd_grad(dims, 1, fake, 7850, fake, fake, 1, 1, fake, None, 0x1000, 16, None) == -3
+    lib.easgd_mlp_round.argtypes = [ip, ctypes.c_int, vp, vp, vp, sz, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp, f, f, f, vp, sz, vp]
+    big = 1 << 30
+    assert lib.easgd_mlp_round(dims, 1, fake, None, None, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, big, None) == -1
+    assert b"NULL" in lib.easgd_last_error()
+    assert lib.easgd_mlp_round(dims, 1, None, None, fake, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, big, None) == -1
+    assert lib.easgd_mlp_round(dims, 1, fake, None, fake, 7000, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, big, None) == -1
+    lib.easgd_grad_workspace_bytes.restype = ctypes.c_size_t
+    short = lib.easgd_grad_workspace_bytes(dims, 1, 1, 1)     # enough for easgd_grad, not for the whole round
+    assert lib.easgd_mlp_round(dims, 1, fake, None, fake, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, short, None) == -3
     many = (ctypes.c_int * 2)(784, 5000)
     assert lib.easgd_grad(many, 1, fake, 784 * 5000 + 5000, fake, fake, 1, 1, fake, None, 0x1000, 1 << 30, None) == -1
 
@@ -78,4 +92,6 @@ def test_options_roundtrip(lib):
     assert lib.easgd_set_option(3, 5) == -1
     assert lib.easgd_set_option(99, 1) == -1
     assert lib.easgd_set_option(3, old) == 0
+    assert lib.easgd_get_option(5) == 1 and lib.easgd_set_option(5, 3) == -1
+    assert lib.easgd_set_option(5, 2) == 0 and lib.easgd_get_option(5) == 2 and lib.easgd_set_option(5, 1) == 0
     assert lib.easgd_version() >= 100

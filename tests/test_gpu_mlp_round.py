@@ -1,0 +1,150 @@
+"""HIP easgd_mlp_round (the whole round in one call, the elastic update fused into backward propagation)
+through the C ABI: against the two-call path it must reproduce, and against the CPU oracle's update rules."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_util import PER_ROUND_TOL, normwise, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+F = np.float32
+ETA, RHO, DELTA = 0.05, 0.1, 0.9
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import paper_1708_02983_amd as hip
+    hip.lib()
+    return hip
+
+
+def _state(dims, P, b, seed, ld_pad=4):
+    """Replicas that have drifted apart, a center of its own and non-zero momentum buffers; NaN padding."""
+    N = workloads.mlp_num_params(dims)
+    wl = workloads.Workload("t", P=P, eta=ETA, rho=RHO, rounds=1, dims=tuple(dims), batch=b, N=N)
+    w0 = workloads.init_packed_weights(wl, seed=seed)
+    ld = workloads.round_up(N, 4) + ld_pad
+    rng = np.random.default_rng(seed)
+    W = workloads.replicate(w0, P, ld)
+    W[:, :N] += (rng.standard_normal((P, N)) * 0.02).astype(F)
+    Wc = (w0 + (rng.standard_normal(N) * 0.01).astype(F)).astype(F)
+    V = workloads.replicate((rng.standard_normal(N) * 0.001).astype(F), P, ld)
+    V[:, :N] += (rng.standard_normal((P, N)) * 0.001).astype(F)
+    X, y = workloads.minibatch(wl, 0, seed=seed)
+    return N, ld, W, V, Wc, X, y
+
+
+# tiny; softmax regression; widths that force the scalar loaders; batch ragged against the MFMA tile;
+# several hidden layers; enough workers for every tile route; a wide last layer
+CASES = [
+    ((5, 4, 3), 2, 3),
+    ((784, 10), 4, 64),
+    ((33, 17, 10), 3, 25),
+    ((50, 70, 30, 7), 9, 100),
+    ((784, 256, 128, 10), 3, 100),
+    ((512, 384, 10), 40, 128),
+    ((130, 1000), 2, 9),
+]
+
+
+@pytest.mark.parametrize("momentum", [False, True], ids=["easgd", "measgd"])
+@pytest.mark.parametrize("dims,P,b", CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_fused_round_equals_gradient_then_update(hip, dims, P, b, momentum):
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=31)
+    dX, dy = to_dev(X), to_dev(y)
+    # reference: the two calls
+    rW, rV, rWc = to_dev(W), to_dev(V), to_dev(Wc)
+    rG = torch.full_like(rW, float("nan")); rloss = torch.empty(P, device="cuda")
+    hip.easgd_grad(dims, rW, dX, dy, rG, rloss)
+    if momentum:
+        hip.measgd_round(rW, rV, rG, rWc, ETA, RHO, DELTA, N=N)
+    else:
+        hip.easgd_sync_round(rW, rG, rWc, ETA, RHO, N=N)
+    G = to_host(rG)
+    # the oracle's update rules applied to the same gradients
+    oW, oV, oWc = W.copy(), V.copy(), Wc.copy()
+    if momentum:
+        oracle.measgd_round(oW, oV, G, oWc, F(ETA), F(RHO), F(DELTA), N=N)
+    else:
+        oracle.easgd_round(oW, G, oWc, F(ETA), F(RHO), N=N)
+    old = hip.get_option(hip.OPT_ROUND_OVERLAP)
+    try:
+        for keep_g, overlap in ((True, 0), (False, 0), (True, 2), (False, 2)):
+            hip.set_option(hip.OPT_ROUND_OVERLAP, overlap)
+            fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
+            fG = torch.full_like(fW, float("nan")) if keep_g else None
+            floss = torch.empty(P, device="cuda")
+            hip.easgd_mlp_round(dims, fW, fWc, dX, dy, ETA, RHO, V=fV if momentum else None, delta=DELTA,
+                                G=fG, loss=floss)
+            what = f"keep_g={keep_g} overlap={overlap}"
+            if keep_g:      # same products, same accumulators: the stored gradient is the same bits
+                np.testing.assert_array_equal(to_host(fG), G, err_msg=what)
+            np.testing.assert_array_equal(to_host(floss), to_host(rloss), err_msg=what)
+            # the worker rule is element-wise on the same inputs: the same bits as the streaming kernel
+            np.testing.assert_array_equal(to_host(fW), to_host(rW), err_msg=what)
+            # the center sums the workers in ascending order; the streaming kernel uses another fixed
+            # order when N is small and P >= 4, so the two may differ by rounding
+            assert normwise(to_host(fWc), to_host(rWc)) <= 1e-6, what
+            assert normwise(to_host(fW)[:, :N], oW[:, :N]) <= PER_ROUND_TOL, what
+            assert normwise(to_host(fWc), oWc) <= PER_ROUND_TOL, what
+            assert np.isnan(to_host(fW)[:, N:]).all(), what          # padding is never written
+            if momentum:
+                np.testing.assert_array_equal(to_host(fV), to_host(rV), err_msg=what)
+                assert normwise(to_host(fV)[:, :N], oV[:, :N]) <= PER_ROUND_TOL, what
+            else:
+                np.testing.assert_array_equal(to_host(fV), V, err_msg=what)   # untouched without momentum
+    finally:
+        hip.set_option(hip.OPT_ROUND_OVERLAP, old)
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3])
+def test_every_tile_shape_gives_the_same_round(hip, tile):
+    dims, P, b = (300, 260, 200, 10), 6, 70
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=32)
+    dX, dy = to_dev(X), to_dev(y)
+    old = hip.get_option(hip.OPT_GEMM_TILE)
+    out = []
+    try:
+        for t in (0, tile):
+            hip.set_option(hip.OPT_GEMM_TILE, t)
+            fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
+            hip.easgd_mlp_round(dims, fW, fWc, dX, dy, ETA, RHO, V=fV, delta=DELTA)
+            out.append((to_host(fW), to_host(fV), to_host(fWc)))
+    finally:
+        hip.set_option(hip.OPT_GEMM_TILE, old)
+    # a tile shape changes the slab depth (the order of the k sums) only: results agree to rounding
+    for a, c in zip(out[0], out[1]):
+        assert normwise(a[..., :N], c[..., :N]) <= 1e-6
+
+
+def test_consecutive_rounds_on_one_stream_and_reproducibility(hip):
+    """Several fused rounds back to back, overlapped and not: the rounds are ordered correctly on the
+    caller's stream (each starts from the previous one's results) and runs are bitwise reproducible."""
+    dims, P, b = (784, 128, 10), 8, 64
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=33)
+    dX, dy = to_dev(X), to_dev(y)
+    old = hip.get_option(hip.OPT_ROUND_OVERLAP)
+    results = []
+    try:
+        for overlap in (0, 2, 2):
+            hip.set_option(hip.OPT_ROUND_OVERLAP, overlap)
+            fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
+            ws = None
+            for _ in range(12):
+                ws = hip.easgd_mlp_round(dims, fW, fWc, dX, dy, ETA, RHO, V=fV, delta=DELTA, workspace=ws)
+            results.append((to_host(fW), to_host(fV), to_host(fWc)))
+    finally:
+        hip.set_option(hip.OPT_ROUND_OVERLAP, old)
+    for other in results[1:]:
+        for a, c in zip(results[0], other):
+            np.testing.assert_array_equal(a, c)
+    # and the same 12 rounds through the two-call path
+    rW, rV, rWc = to_dev(W), to_dev(V), to_dev(Wc)
+    rG = torch.empty_like(rW)
+    for _ in range(12):
+        hip.easgd_grad(dims, rW, dX, dy, rG)
+        hip.measgd_round(rW, rV, rG, rWc, ETA, RHO, DELTA, N=N)
+    assert normwise(results[0][0][:, :N], to_host(rW)[:, :N]) <= 1e-5
+    assert normwise(results[0][2], to_host(rWc)) <= 1e-5

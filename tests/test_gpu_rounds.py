@@ -36,7 +36,11 @@ def _oracle_update(wl, W, V, Wc, G):
         oracle.easgd_round(W, G, Wc, F(wl.eta), F(wl.rho), N=wl.N)
 
 
-def _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws):
+def _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws, path):
+    if path == "one_call":      # the fused whole-round entry point; the gradients are kept for the tie matching
+        hip.easgd_mlp_round(wl.dims, dW, dWc, dX, dy, wl.eta, wl.rho, V=dV if wl.momentum else None,
+                            delta=wl.delta or 0.0, G=dG, workspace=ws)
+        return
     hip.easgd_grad(wl.dims, dW, dX, dy, dG, None, workspace=ws)
     if wl.momentum:
         hip.measgd_round(dW, dV, dG, dWc, wl.eta, wl.rho, wl.delta, N=wl.N)
@@ -44,8 +48,9 @@ def _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws):
         hip.easgd_sync_round(dW, dG, dWc, wl.eta, wl.rho, N=wl.N)
 
 
+@pytest.mark.parametrize("path", ["two_calls", "one_call"])
 @pytest.mark.parametrize("name,rounds,forced_every", [("cfg1", 10, 1), ("cfg2", 50, 10), ("cfg3", 20, 10)])
-def test_training_rounds(hip, name, rounds, forced_every):
+def test_training_rounds(hip, name, rounds, forced_every, path):
     wl = workloads.WORKLOADS[name]
     assert rounds == wl.rounds
     ld = workloads.round_up(wl.N, 4)
@@ -55,7 +60,7 @@ def test_training_rounds(hip, name, rounds, forced_every):
     dW, dWc, dV = to_dev(W), to_dev(Wc), to_dev(V)
     dG = torch.full_like(dW, float("nan"))
     fG = torch.full_like(dW, float("nan"))
-    ws = torch.empty(hip.easgd_grad_workspace_bytes(wl.dims, wl.P, wl.batch), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(hip.easgd_mlp_round_workspace_bytes(wl.dims, wl.P, wl.batch), dtype=torch.uint8, device="cuda")
     worst_forced, ties = 0.0, 0
     losses = []
     for t in range(rounds):
@@ -64,7 +69,7 @@ def test_training_rounds(hip, name, rounds, forced_every):
         if (t % forced_every == 0) or t == rounds - 1:
             # teacher-forced: one GPU round started from the oracle's state of this round
             fW, fWc, fV = to_dev(W), to_dev(Wc), to_dev(V)
-            _gpu_round(hip, wl, fW, fV, fWc, fG, dX, dy, ws)
+            _gpu_round(hip, wl, fW, fV, fWc, fG, dX, dy, ws, path)
             Gf, _, k = match_gradients_all_workers(to_host(fG), wl.dims, W, X, y, PER_ROUND_TOL)
             ties += k
             W1, V1, Wc1 = W.copy(), V.copy(), Wc.copy()
@@ -73,7 +78,7 @@ def test_training_rounds(hip, name, rounds, forced_every):
             if wl.momentum:
                 worst_forced = max(worst_forced, normwise(to_host(fV), V1))
         # free-running: both sides continue from their own state
-        _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws)
+        _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws, path)
         G, loss, k = match_gradients_all_workers(to_host(dG), wl.dims, W, X, y, FREE_RUNNING_MATCH_TOL,
                                                  FREE_RUNNING_NEAR_REL)
         ties += k
@@ -82,7 +87,7 @@ def test_training_rounds(hip, name, rounds, forced_every):
         losses.append(loss.mean())
         if t == 0:      # identical start: the center does not move in the first round
             np.testing.assert_array_equal(to_host(dWc), w0)
-    print(f"{name}: {ties} near-zero ReLU gate(s) resolved; teacher-forced worst {worst_forced:.2e}; "
+    print(f"{name} {path}: {ties} near-zero ReLU gate(s) resolved; teacher-forced worst {worst_forced:.2e}; "
           f"free-running W {normwise(to_host(dW), W):.2e} Wc {normwise(to_host(dWc), Wc):.2e}; "
           f"loss {losses[0]:.4f} -> {losses[-1]:.4f}")
     assert worst_forced <= PER_ROUND_TOL

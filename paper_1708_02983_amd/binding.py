@@ -23,6 +23,7 @@ OPT_UPDATE_NONTEMPORAL = 2
 OPT_UPDATE_GROUPS = 3
 OPT_GEMM_TILE = 4
 OPT_ROUND_OVERLAP = 5
+OPT_GEMM_XCD = 6
 
 
 class EasgdError(RuntimeError):

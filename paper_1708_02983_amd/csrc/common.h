@@ -24,6 +24,7 @@ struct Options {
     long update_groups = 4;
     long gemm_tile = 0;
     long round_overlap = 1;
+    long gemm_xcd = 1;
 };
 Options &options();
 

@@ -47,6 +47,7 @@ struct GemmArgs {
     int splits;
     int tiles_m, tiles_n;
     int P;
+    int xcd_chunk;                      // 0 = plain block order; else grid/8 (see the kernel)
     // elastic epilogues: replica / momentum tiles indexed like C (worker stride c_ws, row stride ldc);
     // the center has the row stride ldc and no worker stride
     float *Wt, *Vt;
@@ -92,8 +93,16 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
     __shared__ __attribute__((aligned(16))) float Bs[2][BK * PITCH_B];
 
     // block -> (worker, split, tile_m, tile_n)
+    // Workgroups go to the eight accelerator dies (XCDs, each with its own L2) in turn, by block index.
+    // With xcd_chunk > 0 the grid is a multiple of 8 and block b works on the logical index
+    // (b % 8) * xcd_chunk + b / 8: each die then owns a run of consecutive tiles, i.e. whole workers,
+    // so that an operand panel shared by the tiles of a worker is fetched into one L2 only.
     const int tiles = p.tiles_m * p.tiles_n;
     int id = blockIdx.x;
+    if (p.xcd_chunk > 0) {
+        id = (id & 7) * p.xcd_chunk + (id >> 3);
+        if (id >= tiles * p.splits * p.P) return;
+    }
     const int tile = id % tiles; id /= tiles;
     const int split = id % p.splits;
     const int w = id / p.splits;

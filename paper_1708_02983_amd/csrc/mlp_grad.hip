@@ -147,7 +147,13 @@ static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
     GemmArgs a = a_in;
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (a.N + BN - 1) / BN;
-    const dim3 grid((unsigned)((size_t)a.tiles_m * a.tiles_n * a.splits * a.P)), block(WM * WN * 64);
+    size_t total = (size_t)a.tiles_m * a.tiles_n * a.splits * a.P;
+    a.xcd_chunk = 0;
+    if (options().gemm_xcd && total >= 64) {
+        total = (total + 7) / 8 * 8;
+        a.xcd_chunk = (int)(total / 8);
+    }
+    const dim3 grid((unsigned)total), block(WM * WN * 64);
     if (vec) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, true, EPI>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI>), grid, block, 0, s, a);
 }

@@ -69,6 +69,10 @@ int easgd_set_option(int option, long value)
         if (value < 0 || value > 2) return easgd::fail(EASGD_EINVAL, "round overlap must be 0, 1 or 2, got %ld", value);
         o.round_overlap = value;
         return EASGD_OK;
+    case EASGD_OPT_GEMM_XCD:
+        if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "gemm xcd must be 0 or 1, got %ld", value);
+        o.gemm_xcd = value;
+        return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
     }
@@ -83,6 +87,7 @@ long easgd_get_option(int option)
     case EASGD_OPT_UPDATE_GROUPS: return o.update_groups;
     case EASGD_OPT_GEMM_TILE: return o.gemm_tile;
     case EASGD_OPT_ROUND_OVERLAP: return o.round_overlap;
+    case EASGD_OPT_GEMM_XCD: return o.gemm_xcd;
     default: return -1;
     }
 }

@@ -148,3 +148,48 @@ def test_consecutive_rounds_on_one_stream_and_reproducibility(hip):
         hip.measgd_round(rW, rV, rG, rWc, ETA, RHO, DELTA, N=N)
     assert normwise(results[0][0][:, :N], to_host(rW)[:, :N]) <= 1e-5
     assert normwise(results[0][2], to_host(rWc)) <= 1e-5
+
+
+@pytest.mark.parametrize("overlap", [0, 2], ids=["one_stream", "two_streams"])
+def test_round_can_be_captured_in_a_hip_graph(hip, overlap):
+    """The call allocates nothing, records no memset and never synchronises, so a caller may capture it.
+    The graph is replayed several times with eager library work and synchronisations in between, and every
+    replay is checked against the same rounds run eagerly (with the second stream in use, its fork and join
+    events become edges of the graph)."""
+    dims, P, b = (784, 96, 10), 6, 32
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=34)
+    dX, dy = to_dev(X), to_dev(y)
+    old = hip.get_option(hip.OPT_ROUND_OVERLAP)
+    hip.set_option(hip.OPT_ROUND_OVERLAP, overlap)
+    try:
+        eW, eV, eWc = to_dev(W), to_dev(V), to_dev(Wc)
+        gW, gV, gWc = to_dev(W), to_dev(V), to_dev(Wc)
+        ws_e = torch.empty(hip.easgd_mlp_round_workspace_bytes(dims, P, b), dtype=torch.uint8, device="cuda")
+        ws_g = torch.empty_like(ws_e)
+
+        def two_rounds(Wt, Vt, Wct, ws):
+            hip.easgd_mlp_round(dims, Wt, Wct, dX, dy, ETA, RHO, V=Vt, delta=DELTA, workspace=ws)
+            hip.easgd_mlp_round(dims, Wt, Wct, dX, dy, ETA, RHO, workspace=ws)
+
+        # eager warm-up on both states: creates the library's stream and events, caches the device properties
+        two_rounds(eW, eV, eWc, ws_e)
+        two_rounds(gW, gV, gWc, ws_g)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            two_rounds(gW, gV, gWc, ws_g)
+        torch.cuda.synchronize()
+        two_rounds(eW, eV, eWc, ws_e)       # what the capture run did, if it ran at all, is not relied upon:
+        gW.copy_(eW); gV.copy_(eV); gWc.copy_(eWc)   # both states restart from the same point
+        for replay in range(4):
+            two_rounds(eW, eV, eWc, ws_e)
+            graph.replay()
+            torch.cuda.synchronize()
+            for a, c in ((eW, gW), (eV, gV), (eWc, gWc)):
+                np.testing.assert_array_equal(to_host(a), to_host(c), err_msg=f"replay {replay}")
+            # eager library work between the replays
+            scratch = torch.empty_like(eW)
+            hip.easgd_grad(dims, eW, dX, dy, scratch)
+            torch.cuda.synchronize()
+    finally:
+        hip.set_option(hip.OPT_ROUND_OVERLAP, old)

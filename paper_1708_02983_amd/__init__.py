@@ -10,10 +10,12 @@ _BINDING_NAMES = (
     "measgd_round", "stream_copy", "stream_triad", "get_option", "set_option", "lib", "version", "LIB_PATH",
     "OPT_UPDATE_BLOCKS_PER_CU", "OPT_UPDATE_NONTEMPORAL", "OPT_UPDATE_GROUPS", "OPT_GEMM_TILE", "OPT_ROUND_OVERLAP", "OPT_GEMM_XCD",
 )
-__all__ = list(_BINDING_NAMES)
+__all__ = list(_BINDING_NAMES) + ["BatchFeeder"]
 
 
 def __getattr__(name):
+    if name == "BatchFeeder":
+        return importlib.import_module(".feeder", __name__).BatchFeeder
     if name in _BINDING_NAMES or name == "binding":
         mod = importlib.import_module(".binding", __name__)
         return mod if name == "binding" else getattr(mod, name)

@@ -1,0 +1,61 @@
+"""Rounds fed from pinned host memory through the double-buffered feeder (the data copy of the next round
+overlaps the current round, Algorithm 3) must give the same bits as rounds whose data is already resident."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_util import to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+F = np.float32
+
+
+def test_host_fed_rounds_equal_resident_rounds():
+    import paper_1708_02983_amd as hip
+    dims, P, b, rounds = (784, 160, 10), 8, 64, 9
+    N = workloads.mlp_num_params(dims)
+    wl = workloads.Workload("t", P=P, eta=0.05, rho=0.1, rounds=rounds, delta=0.9, dims=dims, batch=b, N=N)
+    ld = workloads.round_up(N, 4)
+    w0 = workloads.init_packed_weights(wl)
+    W0 = workloads.replicate(w0, P, ld)
+    batches = [workloads.minibatch(wl, t) for t in range(rounds)]
+
+    def run(feed):
+        W, Wc = to_dev(W0), to_dev(w0.copy())
+        V = torch.zeros_like(W)
+        ws = torch.empty(hip.easgd_mlp_round_workspace_bytes(dims, P, b), dtype=torch.uint8, device="cuda")
+        if not feed:
+            for X, y in batches:
+                hip.easgd_mlp_round(dims, W, Wc, to_dev(X), to_dev(y), wl.eta, wl.rho, V=V, delta=wl.delta, workspace=ws)
+        else:
+            host = [(torch.from_numpy(X).pin_memory(), torch.from_numpy(y).pin_memory()) for X, y in batches]
+            feeder = hip.BatchFeeder(P, b, dims[0])
+            feeder.submit(0, *host[0])
+            for t in range(rounds):
+                if t + 1 < rounds:
+                    feeder.submit((t + 1) % 2, *host[t + 1])      # copy of round t+1 runs beside round t
+                X, y = feeder.acquire(t % 2)
+                hip.easgd_mlp_round(dims, W, Wc, X, y, wl.eta, wl.rho, V=V, delta=wl.delta, workspace=ws)
+                feeder.release(t % 2)
+        torch.cuda.synchronize()
+        return to_host(W), to_host(V), to_host(Wc)
+
+    ref = run(False)
+    for attempt in range(3):        # a missing wait would show as a race, so run it more than once
+        got = run(True)
+        for a, c in zip(ref, got):
+            np.testing.assert_array_equal(a, c, err_msg=f"attempt {attempt}")
+    assert np.isfinite(ref[2]).all() and not np.array_equal(ref[2], w0)
+
+
+def test_feeder_rejects_pageable_memory_and_wrong_shapes():
+    import paper_1708_02983_amd as hip
+    feeder = hip.BatchFeeder(2, 4, 8)
+    X = torch.zeros(2, 4, 8); y = torch.zeros(2, 4, dtype=torch.int32)
+    with pytest.raises(ValueError):
+        feeder.submit(0, X, y)                                   # not pinned
+    with pytest.raises(ValueError):
+        feeder.submit(0, torch.zeros(2, 4, 9).pin_memory(), y.pin_memory())
+    with pytest.raises(ValueError):
+        hip.BatchFeeder(2, 4, 8, slots=1)

@@ -7,9 +7,10 @@ yardstick the HIP library is compared against and shares no code with it.
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.
 
-* ``oracle.elastic``  -- exchange-and-update (C, double arithmetic, fp32 storage)
+* ``oracle.elastic``  -- exchange-and-update (C, double arithmetic, fp32 storage); also the
+  synchronous data-parallel SGD round on replicas (Section 2.3, Section 6.2; Eq. (3),(4))
 * ``oracle.mlp_grad`` -- per-worker minibatch gradient of a dense ReLU MLP with
   softmax cross-entropy (numpy, double arithmetic)
 """
-from .elastic import (build, easgd_round, measgd_round, num_threads)  # noqa: F401
+from .elastic import (build, easgd_round, measgd_round, num_threads, sync_sgd_round)  # noqa: F401
 from .mlp_grad import mlp_grad, mlp_grad_all_workers, layer_slices  # noqa: F401

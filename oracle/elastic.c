@@ -85,3 +85,36 @@ void oracle_measgd_round(float *W, float *V, const float *G, float *Wc,
         Wc[j] = (float)(c + center_coef * sum_diff);                         /* Eq. (2) */
     }
 }
+
+/*
+ * Synchronous data-parallel SGD on P replicas that share one memory.
+ *
+ * Section 2.3 ("Data Parallelism"): the gradients of all workers are summed and the weights move by
+ *     W_{t+1} = W_t - eta * sum_i dW^i_t ,
+ * after which every worker holds the new W.  Section 6.2 (the partitioned chip) is the replicated form
+ * of the same rule: every partition receives the gradient sum and updates its own copy of the weights.
+ * With momentum the sum drives Eq. (3),(4):  V_{t+1} = mu * V_t - eta * sum_i dW^i_t ;  W_{t+1} = W_t + V_{t+1}.
+ *
+ * W, G (and V, or NULL for the plain rule): [P][ld], first N entries of a row valid.  In place on W and V.
+ * The sum is taken over the workers in ascending order, in double.
+ */
+void oracle_sync_sgd_round(float *W, float *V, const float *G,
+                           int P, size_t N, size_t ld, double eta, double mu)
+{
+    long long j;
+#pragma omp parallel for schedule(static)
+    for (j = 0; j < (long long)N; ++j) {
+        double sum_g = 0.0;
+        for (int i = 0; i < P; ++i) sum_g += (double)G[(size_t)i * ld + j];
+        for (int i = 0; i < P; ++i) {
+            const size_t k = (size_t)i * ld + j;
+            if (V) {
+                const float v_new = (float)(mu * (double)V[k] - eta * sum_g);     /* Eq. (3) */
+                V[k] = v_new;
+                W[k] = (float)((double)W[k] + (double)v_new);                      /* Eq. (4) */
+            } else {
+                W[k] = (float)((double)W[k] - eta * sum_g);
+            }
+        }
+    }
+}

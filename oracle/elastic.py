@@ -41,6 +41,9 @@ def _load():
                                             ctypes.c_size_t, ctypes.c_double, ctypes.c_double,
                                             ctypes.c_double, ctypes.c_double]
         lib.oracle_measgd_round.restype = None
+        lib.oracle_sync_sgd_round.argtypes = [f32p, f32p, f32p, ctypes.c_int, ctypes.c_size_t,
+                                              ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
+        lib.oracle_sync_sgd_round.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -92,3 +95,20 @@ def measgd_round(W: np.ndarray, V: np.ndarray, G: np.ndarray, Wc: np.ndarray, et
     cc = float(eta) * float(rho) if center_coef is None else float(center_coef)
     _load().oracle_measgd_round(_ptr(W), _ptr(V), _ptr(G), _ptr(Wc), P, N, ld,
                                 float(eta), float(rho), float(mu), cc)
+
+
+def sync_sgd_round(W: np.ndarray, G: np.ndarray, eta: float, V: Optional[np.ndarray] = None,
+                   mu: float = 0.0, N: Optional[int] = None) -> None:
+    """One round of synchronous data-parallel SGD on P replicas, in place on W[P][ld] (and V):
+    every replica moves by the sum of all workers' gradients (Section 2.3; Section 6.2); with V the
+    sum drives the momentum rule Eq. (3),(4)."""
+    _check("W", W)
+    P, ld = W.shape
+    N = ld if N is None else N
+    _check("G", G, (P, ld))
+    if V is not None:
+        _check("V", V, (P, ld))
+    if ld < N:
+        raise ValueError("ld < N")
+    _load().oracle_sync_sgd_round(_ptr(W), None if V is None else _ptr(V), _ptr(G), P, N, ld,
+                                  float(eta), float(mu))

@@ -193,7 +193,9 @@ def bench_host_fed(hip, wl, steps, warmup):
                     "round t; rounds on a non-default stream, library on one stream"}
 
 
-def bench_update_only(hip, wl, steps, warmup, pool=3):
+def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
+    """rule = "elastic": the workload's EASGD / MEASGD update; "sync_sgd": the synchronous data-parallel SGD
+    round on the same replicas and gradients (every replica moves by the gradient sum)."""
     import torch
     P, N = wl.P, wl.N
     dW = workloads.device_normal((P, N), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 1)
@@ -203,7 +205,9 @@ def bench_update_only(hip, wl, steps, warmup, pool=3):
     Gs = [workloads.device_normal((P, N), workloads.GRADIENT_STD, workloads.DEFAULT_SEED, 100 + t) for t in range(pool)]
 
     def step(t):
-        if wl.momentum:
+        if rule == "sync_sgd":
+            hip.sync_sgd_round(dW, Gs[t % pool], wl.eta / P, V=dV, delta=wl.delta or 0.0)
+        elif wl.momentum:
             hip.measgd_round(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta)
         else:
             hip.easgd_sync_round(dW, Gs[t % pool], dWc, wl.eta, wl.rho)
@@ -219,7 +223,7 @@ def bench_update_only(hip, wl, steps, warmup, pool=3):
         e1[t].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    assert bool(torch.isfinite(dWc).all())
+    assert bool(torch.isfinite(dWc).all()) and bool(torch.isfinite(dW[0, :4096]).all())
     kernel_ms = _sum_ms(e0, e1) / steps
     return {"elapsed_s": elapsed, "ms_per_step": 1e3 * elapsed / steps, "update_ms": kernel_ms}
 
@@ -379,6 +383,20 @@ def main():
             extra[name] = {"workload": DESCRIPTIONS[name], "rounds_per_s": round(100 / r2["elapsed_s"], 2),
                            "ms_per_step": round(r2["ms_per_step"], 4), "roofline": hbm_roofline(w2, r2["update_ms"], ceiling)}
             torch.cuda.empty_cache()
+        # the method's point of comparison on the same replicas: synchronous data-parallel SGD (gradient sum
+        # applied to every copy); per parameter and worker it reads g and W and writes W
+        w4 = workloads.WORKLOADS["cfg4"]
+        r3 = bench_update_only(hip, w4, 100, 5, rule="sync_sgd")
+        sgd_bytes = 12 * w4.P * w4.N
+        gbs = sgd_bytes / (r3["update_ms"] * 1e-3) / 1e9
+        extra["sync_sgd_cfg4_shape"] = {
+            "workload": "synchronous data-parallel SGD round, P=8 replicas x 61M fp32 parameters (sync_sgd_round)",
+            "rounds_per_s": round(100 / r3["elapsed_s"], 2), "ms_per_step": round(r3["ms_per_step"], 4),
+            "roofline": {"bound": "hbm", "kernel": "sync_sgd_vec4_kernel", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                         "algorithmic_bytes_per_launch": sgd_bytes, "avg_launch_ms": round(r3["update_ms"], 4),
+                         "frac_of_triad_ceiling": round(gbs / ceiling, 4)}}
+        torch.cuda.empty_cache()
         line["elastic_update"] = extra
 
     if not args.no_cpu_baseline:

@@ -88,6 +88,23 @@ int measgd_round(float *W, float *V, const float *G, float *Wc,
                  float eta, float rho, float delta, void *stream);
 
 /*
+ * Synchronous data-parallel SGD on the same replicas, the method's point of comparison (Section 2.3,
+ * "Data Parallelism": the gradients of all workers are summed, W <- W - eta * sum_i dW^i, and every worker
+ * receives the new W; Section 6.2: on a partitioned chip every partition receives the gradient sum and
+ * updates its own copy).  With momentum buffers the sum drives Eq. (3),(4).
+ *
+ *   for every parameter j:   s = G[0][j] + G[1][j] + ... + G[P-1][j]          (ascending i, fixed order)
+ *     for every worker i:    W[i][j] <- W[i][j] - eta*s                       (V == NULL)
+ *                            V[i][j] <- delta*V[i][j] - eta*s;  W[i][j] <- W[i][j] + V[i][j]   Eq. (3),(4)
+ *
+ *   W  DEVICE in/out [P][ld];  V  DEVICE in/out [P][ld] or NULL;  G  DEVICE in [P][ld]
+ * Replicas that start equal stay equal bit for bit.  Alignment rule and errors as for easgd_sync_round.
+ */
+int sync_sgd_round(float *W, float *V, const float *G,
+                   int P, size_t N, size_t ld,
+                   float eta, float delta, void *stream);
+
+/*
  * Step (1) of the round (Section 5.1; forward/backward propagation of Section
  * 2.2) for a dense ReLU multilayer perceptron with softmax cross-entropy loss,
  * averaged over the b samples of each worker's minibatch.  Worker i uses its

@@ -43,6 +43,8 @@ def _load() -> ctypes.CDLL:
     lib.easgd_sync_round.restype = i
     lib.measgd_round.argtypes = [vp, vp, vp, vp, i, sz, sz, f, f, f, vp]
     lib.measgd_round.restype = i
+    lib.sync_sgd_round.argtypes = [vp, vp, vp, i, sz, sz, f, f, vp]
+    lib.sync_sgd_round.restype = i
     ip = ctypes.POINTER(ctypes.c_int)
     lib.easgd_grad_workspace_bytes.argtypes = [ip, i, i, i]
     lib.easgd_grad_workspace_bytes.restype = sz
@@ -120,6 +122,16 @@ def measgd_round(W, V, G, Wc, eta: float, rho: float, delta: float, N: Optional[
     _check(_lib.measgd_round(_dev("W", W, torch.float32, need), _dev("V", V, torch.float32, need),
                              _dev("G", G, torch.float32, need), _dev("Wc", Wc, torch.float32, N),
                              P, N, ld, eta, rho, delta, _stream(stream)))
+
+
+def sync_sgd_round(W, G, eta: float, V=None, delta: float = 0.0, N: Optional[int] = None, stream=None) -> None:
+    """Synchronous data-parallel SGD on the replicas: every replica moves by the sum of all gradients
+    (Section 2.3, Section 6.2); V selects the momentum rule Eq. (3),(4)."""
+    P, ld, N = _replica_shape(W, N)
+    need = (P - 1) * ld + N
+    _check(_lib.sync_sgd_round(_dev("W", W, torch.float32, need),
+                               None if V is None else _dev("V", V, torch.float32, need),
+                               _dev("G", G, torch.float32, need), P, N, ld, eta, delta, _stream(stream)))
 
 
 def _dims(dims: Sequence[int]):

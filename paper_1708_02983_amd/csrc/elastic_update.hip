@@ -288,6 +288,138 @@ int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t 
     return check_launch("center rule");
 }
 
+// ---- synchronous data-parallel SGD on the replicas (Section 2.3; the partitioned form of Section 6.2) ----
+// Every replica moves by the SUM of all workers' gradients: s = g_0 + g_1 + ... (ascending, one thread per
+// parameter group, so the order is fixed), then W_i <- W_i - eta*s, or with momentum Eq. (3),(4)
+// V_i <- mu*V_i - eta*s, W_i <- W_i + V_i.  Same streaming skeleton as the elastic update: the gradients of
+// all workers are read first (they must all be known before any replica moves), then each replica is
+// read and written once.
+template <bool MOM, typename T>
+__device__ __forceinline__ void sgd_rule(T &w, T &v, T s, float eta, float mu)
+{
+    if constexpr (MOM) {
+        v = mu * v - eta * s;                 // Eq. (3)
+        w = w + v;                            // Eq. (4)
+    } else {
+        w = w - eta * s;
+    }
+}
+
+template <bool MOM, bool NT, int GROUPS>
+__global__ __launch_bounds__(256) void sync_sgd_vec4_kernel(float *__restrict__ Wp, float *__restrict__ Vp,
+                                                            const float *__restrict__ Gp, int P, size_t N, size_t ld,
+                                                            float eta, float mu)
+{
+    f32x4 *__restrict__ W = (f32x4 *)Wp;
+    f32x4 *__restrict__ V = (f32x4 *)Vp;
+    const f32x4 *__restrict__ G = (const f32x4 *)Gp;
+    const size_t n4 = N / 4, ld4 = ld / 4;
+    constexpr size_t TILE = (size_t)GROUPS * 256;
+    const size_t n_tiles = (n4 + TILE - 1) / TILE;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const size_t j0 = t * TILE + threadIdx.x;
+        f32x4 s[GROUPS];
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) s[q] = zero;
+        for (int i = 0; i < P; ++i) {                 // ascending worker order: fixed summation order
+            const size_t row = (size_t)i * ld4;
+            f32x4 g[GROUPS];
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * 256;
+                g[q] = (j < n4) ? stream_load<NT>(G + row + j) : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) s[q] += g[q];
+        }
+        for (int i = 0; i < P; ++i) {
+            const size_t row = (size_t)i * ld4;
+            f32x4 w[GROUPS], v[GROUPS];
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * 256;
+                if (j < n4) {
+                    w[q] = stream_load<NT>(W + row + j);
+                    if constexpr (MOM) v[q] = stream_load<NT>(V + row + j);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * 256;
+                if (j < n4) {
+                    sgd_rule<MOM>(w[q], v[q], s[q], eta, mu);
+                    stream_store<NT>(W + row + j, w[q]);
+                    if constexpr (MOM) stream_store<NT>(V + row + j, v[q]);
+                }
+            }
+        }
+    }
+    const size_t tail = N - n4 * 4;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail) {
+        const size_t k = n4 * 4 + threadIdx.x;
+        float s = 0.f;
+        for (int i = 0; i < P; ++i) s += Gp[(size_t)i * ld + k];
+        for (int i = 0; i < P; ++i) {
+            float w = Wp[(size_t)i * ld + k], v = MOM ? Vp[(size_t)i * ld + k] : 0.f;
+            sgd_rule<MOM>(w, v, s, eta, mu);
+            Wp[(size_t)i * ld + k] = w;
+            if constexpr (MOM) Vp[(size_t)i * ld + k] = v;
+        }
+    }
+}
+
+// Any alignment: one thread per parameter.
+template <bool MOM>
+__global__ __launch_bounds__(256) void sync_sgd_scalar_kernel(float *__restrict__ W, float *__restrict__ V,
+                                                              const float *__restrict__ G, int P, size_t N, size_t ld,
+                                                              float eta, float mu)
+{
+    for (size_t k = (size_t)blockIdx.x * 256 + threadIdx.x; k < N; k += (size_t)gridDim.x * 256) {
+        float s = 0.f;
+        for (int i = 0; i < P; ++i) s += G[(size_t)i * ld + k];
+        for (int i = 0; i < P; ++i) {
+            float w = W[(size_t)i * ld + k], v = MOM ? V[(size_t)i * ld + k] : 0.f;
+            sgd_rule<MOM>(w, v, s, eta, mu);
+            W[(size_t)i * ld + k] = w;
+            if constexpr (MOM) V[(size_t)i * ld + k] = v;
+        }
+    }
+}
+
+template <bool MOM, bool NT>
+static void launch_sync_sgd(int groups, dim3 grid, hipStream_t s, float *W, float *V, const float *G, int P, size_t N,
+                            size_t ld, float eta, float mu)
+{
+    if (groups == 4) hipLaunchKernelGGL((sync_sgd_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else if (groups == 2) hipLaunchKernelGGL((sync_sgd_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else hipLaunchKernelGGL((sync_sgd_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+}
+
+template <bool MOM>
+static int sync_sgd(float *W, float *V, const float *G, int P, size_t N, size_t ld, float eta, float mu, void *stream)
+{
+    const char *name = "sync_sgd_round";
+    if (!W || !G) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
+    if (P < 1) return fail(EASGD_EINVAL, "%s: P must be >= 1, got %d", name, P);
+    if (N == 0) return fail(EASGD_EINVAL, "%s: N must be >= 1", name);
+    if (ld < N) return fail(EASGD_EINVAL, "%s: ld (%zu) < N (%zu)", name, ld, N);
+    clear_error();
+    const Options &opt = options();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool vec = aligned16(W) && aligned16(G) && (!MOM || aligned16(V)) && (ld % 4 == 0);
+    size_t groups = (size_t)opt.update_groups;
+    while (groups > 1 && N / 4 / (groups * 256) < (size_t)(4 * num_cus())) groups /= 2;
+    size_t blocks = vec ? (N / 4 + groups * 256 - 1) / (groups * 256) : (N + 255) / 256;
+    if (blocks == 0) blocks = 1;
+    if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
+    const dim3 grid((unsigned)blocks);
+    if (!vec) hipLaunchKernelGGL((sync_sgd_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else if (opt.update_nontemporal) launch_sync_sgd<MOM, true>((int)groups, grid, s, W, V, G, P, N, ld, eta, mu);
+    else launch_sync_sgd<MOM, false>((int)groups, grid, s, W, V, G, P, N, ld, eta, mu);
+    return check_launch(name);
+}
+
 int elastic_range(float *W, float *V, const float *G, float *Wc, int P, size_t N, size_t ld,
                   float eta, float rho, float delta, void *stream)
 {
@@ -309,6 +441,12 @@ int measgd_round(float *W, float *V, const float *G, float *Wc, int P, size_t N,
                  float eta, float rho, float delta, void *stream)
 {
     return easgd::elastic_round<true>(W, V, G, Wc, P, N, ld, eta, rho, delta, stream);
+}
+
+int sync_sgd_round(float *W, float *V, const float *G, int P, size_t N, size_t ld, float eta, float delta, void *stream)
+{
+    return V ? easgd::sync_sgd<true>(W, V, G, P, N, ld, eta, delta, stream)
+             : easgd::sync_sgd<false>(W, nullptr, G, P, N, ld, eta, 0.0f, stream);
 }
 
 }  // extern "C"

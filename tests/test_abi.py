@@ -63,6 +63,13 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert lib.easgd_sync_round(fake, fake, fake, 1, 8, 4, 0.1, 0.1, None) == -1
     assert b"ld" in lib.easgd_last_error()
     assert lib.measgd_round(fake, None, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+    lib.sync_sgd_round.argtypes = [vp, vp, vp, ctypes.c_int, sz, sz, f, f, vp]
+    assert lib.sync_sgd_round(None, None, fake, 1, 4, 4, 0.1, 0.0, None) == -1
+    assert lib.sync_sgd_round(fake, None, None, 1, 4, 4, 0.1, 0.0, None) == -1
+    assert lib.sync_sgd_round(fake, None, fake, 0, 4, 4, 0.1, 0.0, None) == -1
+    assert lib.sync_sgd_round(fake, None, fake, 1, 0, 4, 0.1, 0.0, None) == -1
+    assert lib.sync_sgd_round(fake, fake, fake, 1, 8, 4, 0.1, 0.9, None) == -1
+    assert b"sync_sgd_round" in lib.easgd_last_error()
     ip = ctypes.POINTER(ctypes.c_int)
     lib.easgd_grad.argtypes = [ip, ctypes.c_int, vp, sz, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
     dims = (ctypes.c_int * 2)(784, 10)

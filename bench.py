@@ -156,12 +156,13 @@ def bench_host_fed(hip, wl, steps, warmup):
             feeder.release(t % 2)
 
     # Measured on this device: the copy overlaps the round only when the round runs on a stream of its own
-    # (not the default stream) and the library keeps to that one stream; with the library's second stream in
-    # use as well, the event waits between three streams serialise the copy and the round.  HIP also
+    # (not the default stream) and the library keeps to that one stream (the center rule on extra blocks of a
+    # forward launch, never on the library's second stream); with three streams tied by events the copy and
+    # the round serialise.  HIP also
     # multiplexes streams onto a few hardware queues (4 per process here), and a copy stream and a compute
     # stream that share a queue run one after the other: short trials pick a pair of streams that does not.
     old = hip.get_option(hip.OPT_ROUND_OVERLAP)
-    hip.set_option(hip.OPT_ROUND_OVERLAP, 0)
+    hip.set_option(hip.OPT_ROUND_OVERLAP, 3)
     try:
         best, done = None, 0
         for _ in range(6):

@@ -179,10 +179,11 @@ typedef enum {
     EASGD_OPT_UPDATE_GROUPS        = 3,  /* 128-bit groups per thread and worker: 1, 2 or 4 (default); tile = groups*1024 parameters */
     EASGD_OPT_GEMM_TILE            = 4,  /* block tile of the wide matrix products of easgd_grad: 0 = chosen per product (default),
                                             1 = 128x128, 2 = 64x64, 3 = 128x64 */
-    EASGD_OPT_ROUND_OVERLAP        = 5,  /* easgd_mlp_round: the center rule may run on a second stream of the library, beside
-                                            forward propagation: 0 = never (every kernel on the caller's stream), 1 = when
-                                            P*N >= 2^24, below which ordering the two streams costs more than it hides
-                                            (default), 2 = always */
+    EASGD_OPT_ROUND_OVERLAP        = 5,  /* easgd_mlp_round, where the center rule runs: 0 = a kernel of its own on the caller's
+                                            stream; 2 = the same on a second stream of the library, beside forward propagation;
+                                            3 = on extra blocks of the first forward product's launch; 1 = chosen per call
+                                            (default): 3 when that launch leaves room on the chip, else 2 when P*N >= 2^24
+                                            (below which ordering two streams costs more than it hides), else 0 */
     EASGD_OPT_GEMM_XCD             = 6   /* 1 = the blocks of a matrix product are renumbered so that each of the eight dies
                                             works on whole workers (default), 0 = plain block order */
 } easgd_option;

@@ -237,43 +237,12 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
     return check_launch(name);
 }
 
-// Eq. (2) alone, ahead of the worker rules: Wc[j] <- c + alpha * sum_i (W_i[j] - c) with c = Wc[j], workers in
-// ascending order (the order of the fused kernels above), while the time-t value c is saved to old[j] for the
-// worker rules that run later in the round.  W is read with ordinary loads: the same values are needed again soon.
+// Eq. (2) alone as a kernel of its own (see center_rule_block).
 template <typename T>
 __global__ __launch_bounds__(256) void center_rule_kernel(const float *__restrict__ Wp, float *__restrict__ Wcp,
                                                           float *__restrict__ oldp, int P, size_t N, size_t ld, float alpha)
 {
-    constexpr size_t LANES = sizeof(T) / sizeof(float);
-    const T *__restrict__ W = (const T *)Wp;
-    T *__restrict__ Wc = (T *)Wcp;
-    T *__restrict__ old = (T *)oldp;
-    const size_t n = N / LANES, ldt = ld / LANES;
-    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (j < n) {
-        const T c = Wc[j];
-        T acc = c - c;
-        int i = 0;
-        for (; i + 4 <= P; i += 4) {
-            T w[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) w[u] = W[(size_t)(i + u) * ldt + j];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc += w[u] - c;
-        }
-        for (; i < P; ++i) acc += W[(size_t)i * ldt + j] - c;
-        old[j] = c;
-        Wc[j] = c + alpha * acc;
-    }
-    const size_t tail = N - n * LANES;        // only for T = f32x4
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail) {
-        const size_t k = n * LANES + threadIdx.x;
-        const float c = Wcp[k];
-        float acc = 0.f;
-        for (int i = 0; i < P; ++i) acc += Wp[(size_t)i * ld + k] - c;
-        oldp[k] = c;
-        Wcp[k] = c + alpha * acc;
-    }
+    center_rule_block<T>(Wp, Wcp, oldp, P, N, ld, alpha, blockIdx.x, gridDim.x, threadIdx.x);
 }
 
 int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t ld, float alpha, void *stream)

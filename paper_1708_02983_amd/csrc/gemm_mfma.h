@@ -53,6 +53,9 @@ struct GemmArgs {
     float *Wt, *Vt;
     const float *center;
     float eta, rho, alpha, delta;
+    // extra blocks at the end of the grid that run the center rule beside the product (bandwidth-bound
+    // work in the shadow of matrix-core-bound work, without a second stream); ctr.blocks == 0: none
+    CenterJob ctr;
 };
 
 // Four elements idx0..idx0+3 along the contiguous axis of a row that starts at `row`.
@@ -97,6 +100,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
     // With xcd_chunk > 0 the grid is a multiple of 8 and block b works on the logical index
     // (b % 8) * xcd_chunk + b / 8: each die then owns a run of consecutive tiles, i.e. whole workers,
     // so that an operand panel shared by the tiles of a worker is fetched into one L2 only.
+    if (p.ctr.blocks > 0 && blockIdx.x >= p.ctr.first_block) {         // uniform for the block
+        const size_t b = blockIdx.x - p.ctr.first_block;
+        if (p.ctr.vec) center_rule_block<f32x4>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
+        else center_rule_block<float>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
+        return;
+    }
     const int tiles = p.tiles_m * p.tiles_n;
     int id = blockIdx.x;
     if (p.xcd_chunk > 0) {

@@ -153,6 +153,11 @@ static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
         total = (total + 7) / 8 * 8;
         a.xcd_chunk = (int)(total / 8);
     }
+    static_assert(WM * WN * 64 == 256, "the center rule's extra blocks assume 256 threads");
+    if (a.ctr.blocks > 0) {
+        a.ctr.first_block = (unsigned)total;
+        total += a.ctr.blocks;
+    }
     const dim3 grid((unsigned)total), block(WM * WN * 64);
     if (vec) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, true, EPI>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI>), grid, block, 0, s, a);
@@ -178,6 +183,21 @@ static void launch_gemm(const GemmArgs &a, bool vec, bool large_ok, hipStream_t 
 }
 
 static inline bool mult4(size_t x) { return (x & 3u) == 0; }
+
+// Whether the launch of a forward product (M x N per worker, P workers, `splits` K splits) leaves room on the
+// chip for extra blocks that do bandwidth-bound work beside it.  Mirrors launch_gemm: the 128x32 and 64x64
+// tiles use few enough registers and LDS for four blocks per compute unit, the 128x128 tile for two, and it
+// is chosen exactly when its blocks already fill those.
+static bool forward_launch_has_room(int M, int N, int P, int splits)
+{
+    const size_t cus = (size_t)num_cus();
+    if (N <= 32) return (size_t)((M + 127) / 128) * splits * P <= 3 * cus;
+    long tile = options().gemm_tile;
+    const size_t big = (size_t)((M + 127) / 128) * ((N + 127) / 128) * splits * P;
+    if (tile == 0) tile = (big >= 2 * cus) ? 1 : 2;
+    if (tile != 2) return false;
+    return (size_t)((M + 63) / 64) * ((N + 63) / 64) * splits * P <= 3 * cus;
+}
 
 // Elastic update fused into the backward pass.  Eq. (2) runs first and saves the time-t
 // center in the workspace for the worker rules; the worker rule is the epilogue of each
@@ -300,11 +320,18 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     float *old_center = step ? reinterpret_cast<float *>(ws + pl.center_off) : nullptr;
     std::unique_lock<std::mutex> lane_guard;
     SideLane *lane = nullptr;
+    bool attach_center = false;
     if (step) {
-        // ordering two streams against each other costs some tens of microseconds of latency: by default the
-        // second stream is used only when the center rule has enough to read to be worth hiding
+        // Where Eq. (2) runs (EASGD_OPT_ROUND_OVERLAP): 0 = a kernel of its own on the caller's stream, 2 = the
+        // same on the library's second stream, beside forward propagation, 3 = on extra blocks of the first
+        // forward product's launch.  1 (default) chooses: the extra blocks when that launch leaves room on the
+        // chip (they then fill idle wave slots, no stream is involved); else the second stream when the rule has
+        // enough to read to be worth the tens of microseconds that ordering two streams costs; else its own kernel.
         const long overlap = options().round_overlap;
-        if (overlap == 2 || (overlap == 1 && (size_t)P * pl.N >= ((size_t)1 << 24))) {
+        const int splits0 = (L == 1) ? pl.splits : 1;
+        const bool room = forward_launch_has_room(b, dims[1], P, splits0);
+        attach_center = (overlap == 3) || (overlap == 1 && room);
+        if (!attach_center && (overlap == 2 || (overlap == 1 && (size_t)P * pl.N >= ((size_t)1 << 24)))) {
             lane_guard = std::unique_lock<std::mutex>(side_mutex);
             lane = side_lane();
         }
@@ -316,8 +343,10 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
             rc = center_range(step->W, step->Wc, old_center, P, pl.N, ld, alpha, lane->stream);
             if (rc == EASGD_OK && hipEventRecord(lane->join, lane->stream) != hipSuccess)
                 rc = fail(EASGD_ELAUNCH, "%s: stream join failed", name);
-        } else {
+        } else if (!attach_center) {
             rc = center_range(step->W, step->Wc, old_center, P, pl.N, ld, alpha, s);
+        } else {
+            rc = EASGD_OK;
         }
         if (rc != EASGD_OK) return rc;
     }
@@ -334,6 +363,14 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         a.splits = last ? pl.splits : 1;
         a.k_per_split = last ? pl.k_per_split : ((a.K + 63) / 64 * 64);
         a.c_ss = (size_t)P * b * d_out;
+        if (attach_center && l == 0) {
+            const bool cvec = aligned16(step->W) && aligned16(step->Wc) && aligned16(old_center) && (ld % 4 == 0);
+            const size_t cblocks = (cvec ? pl.N / 4 : pl.N) / 256 + 1;
+            if (cblocks > 0x3fffffffu) return fail(EASGD_ERANGE, "%s: N too large", name);
+            a.ctr.W = step->W; a.ctr.Wc = step->Wc; a.ctr.old = old_center;
+            a.ctr.N = pl.N; a.ctr.ld = ld; a.ctr.P = P; a.ctr.vec = cvec ? 1 : 0;
+            a.ctr.alpha = step->eta * step->rho; a.ctr.blocks = (unsigned)cblocks;
+        }
         const bool vec = base_vec && mult4(d_in) && mult4(d_out) && mult4(pl.off[l]);
         if (last) launch_gemm<K_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, true, s);
         else launch_gemm<K_CONTIG, MN_CONTIG, EPI_RELU>(a, vec, true, s);

@@ -66,7 +66,7 @@ int easgd_set_option(int option, long value)
         o.gemm_tile = value;
         return EASGD_OK;
     case EASGD_OPT_ROUND_OVERLAP:
-        if (value < 0 || value > 2) return easgd::fail(EASGD_EINVAL, "round overlap must be 0, 1 or 2, got %ld", value);
+        if (value < 0 || value > 3) return easgd::fail(EASGD_EINVAL, "round overlap must be in [0,3], got %ld", value);
         o.round_overlap = value;
         return EASGD_OK;
     case EASGD_OPT_GEMM_XCD:

@@ -99,6 +99,6 @@ def test_options_roundtrip(lib):
     assert lib.easgd_set_option(3, 5) == -1
     assert lib.easgd_set_option(99, 1) == -1
     assert lib.easgd_set_option(3, old) == 0
-    assert lib.easgd_get_option(5) == 1 and lib.easgd_set_option(5, 3) == -1
+    assert lib.easgd_get_option(5) == 1 and lib.easgd_set_option(5, 4) == -1
     assert lib.easgd_set_option(5, 2) == 0 and lib.easgd_get_option(5) == 2 and lib.easgd_set_option(5, 1) == 0
     assert lib.easgd_version() >= 100

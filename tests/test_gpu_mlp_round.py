@@ -71,7 +71,7 @@ def test_fused_round_equals_gradient_then_update(hip, dims, P, b, momentum):
         oracle.easgd_round(oW, G, oWc, F(ETA), F(RHO), N=N)
     old = hip.get_option(hip.OPT_ROUND_OVERLAP)
     try:
-        for keep_g, overlap in ((True, 0), (False, 0), (True, 2), (False, 2)):
+        for keep_g, overlap in ((True, 0), (False, 0), (True, 2), (False, 2), (True, 3), (False, 3), (False, 1)):
             hip.set_option(hip.OPT_ROUND_OVERLAP, overlap)
             fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
             fG = torch.full_like(fW, float("nan")) if keep_g else None
@@ -128,7 +128,7 @@ def test_consecutive_rounds_on_one_stream_and_reproducibility(hip):
     old = hip.get_option(hip.OPT_ROUND_OVERLAP)
     results = []
     try:
-        for overlap in (0, 2, 2):
+        for overlap in (0, 2, 2, 3, 1):
             hip.set_option(hip.OPT_ROUND_OVERLAP, overlap)
             fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
             ws = None
@@ -150,7 +150,7 @@ def test_consecutive_rounds_on_one_stream_and_reproducibility(hip):
     assert normwise(results[0][2], to_host(rWc)) <= 1e-5
 
 
-@pytest.mark.parametrize("overlap", [0, 2], ids=["one_stream", "two_streams"])
+@pytest.mark.parametrize("overlap", [0, 2, 3], ids=["one_stream", "two_streams", "extra_blocks"])
 def test_round_can_be_captured_in_a_hip_graph(hip, overlap):
     """The call allocates nothing, records no memset and never synchronises, so a caller may capture it.
     The graph is replayed several times with eager library work and synchronisations in between, and every

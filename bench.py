@@ -296,26 +296,39 @@ def cpu_baseline(wl, budget_s=12.0):
         return {"value": round(done / el, 4), "unit": "rounds/s", "cores": cores, "kind": "oracle",
                 "sample": f"{done} whole rounds (numpy fp64 gradient of all {wl.P} workers + C elastic update) "
                           f"of the same workload in {el:.1f} s"}
-    # update-only: a 1/8 slice of the parameter index (the update is independent per parameter)
+    # update-only: a 1/8 slice of the parameter index (the update is independent per parameter), first on all
+    # host cores, then on a single thread (the plain scalar loop)
     frac = 8
     n = wl.N // frac
     W, Wc = workloads.update_state(wl.P, n)
     G = workloads.update_gradients(wl.P, n, 0)
     V = np.zeros_like(W)
-    done, t0 = 0, time.perf_counter()
-    while True:
-        if wl.momentum:
-            oracle.measgd_round(W, V, G, Wc, F(wl.eta), F(wl.rho), F(wl.delta))
-        else:
-            oracle.easgd_round(W, G, Wc, F(wl.eta), F(wl.rho))
-        done += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s / 2 or done >= 400:
-            break
+
+    def timed(budget, cap):
+        done, t0 = 0, time.perf_counter()
+        while True:
+            if wl.momentum:
+                oracle.measgd_round(W, V, G, Wc, F(wl.eta), F(wl.rho), F(wl.delta))
+            else:
+                oracle.easgd_round(W, G, Wc, F(wl.eta), F(wl.rho))
+            done += 1
+            el = time.perf_counter() - t0
+            if el >= budget or done >= cap:
+                return done, el
+
+    done, el = timed(budget_s / 2, 400)
+    oracle.set_num_threads(1)
+    try:
+        done1, el1 = timed(budget_s / 4, 50)
+    finally:
+        oracle.set_num_threads(0)
     return {"value": round(done / el / frac, 4), "unit": "rounds/s", "cores": cores, "kind": "oracle",
             "sample": f"{done} rounds on a 1/{frac} slice of the parameter index ({n} of {wl.N} parameters, all "
                       f"{wl.P} replicas) in {el:.1f} s; rate divided by {frac}",
-            "GBs": round(update_bytes(wl) / frac * done / el / 1e9, 2)}
+            "GBs": round(update_bytes(wl) / frac * done / el / 1e9, 2),
+            "single_thread": {"value": round(done1 / el1 / frac, 4), "unit": "rounds/s",
+                              "GBs": round(update_bytes(wl) / frac * done1 / el1 / 1e9, 2),
+                              "sample": f"{done1} rounds on the same slice in {el1:.1f} s"}}
 
 
 # ---------------------------------------------------------------------------

@@ -12,5 +12,5 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 * ``oracle.mlp_grad`` -- per-worker minibatch gradient of a dense ReLU MLP with
   softmax cross-entropy (numpy, double arithmetic)
 """
-from .elastic import (build, easgd_round, measgd_round, num_threads, sync_sgd_round)  # noqa: F401
+from .elastic import (build, easgd_round, measgd_round, num_threads, set_num_threads, sync_sgd_round)  # noqa: F401
 from .mlp_grad import mlp_grad, mlp_grad_all_workers, layer_slices  # noqa: F401

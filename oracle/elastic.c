@@ -40,6 +40,16 @@ int oracle_num_threads(void)
 #endif
 }
 
+/* Number of threads the loops below use from now on (n < 1: all cores again); for timing only. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    omp_set_num_threads(n >= 1 ? n : omp_get_num_procs());
+#else
+    (void)n;
+#endif
+}
+
 /* W, G: [P][ld] (first N entries of each row are valid); Wc: [N]. In place on W, Wc. */
 void oracle_easgd_round(float *W, const float *G, float *Wc,
                         int P, size_t N, size_t ld,

@@ -45,12 +45,19 @@ def _load():
                                               ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
         lib.oracle_sync_sgd_round.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        lib.oracle_set_num_threads.restype = None
         _lib = lib
     return _lib
 
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads used by the C loops from now on (n < 1: all cores); only the timing of the oracle uses this."""
+    _load().oracle_set_num_threads(int(n))
 
 
 def _ptr(a: np.ndarray):

@@ -341,7 +341,7 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--no-extras", action="store_true", help="skip the cfg4/cfg5 elastic-update legs of the default run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--round-overlap", type=int, default=None, choices=(0, 1, 2),
+    ap.add_argument("--round-overlap", type=int, default=None, choices=(0, 1, 2, 3),
                     help="library option EASGD_OPT_ROUND_OVERLAP for the one-call path (default: the library's)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -11,6 +11,13 @@
 //   inputs    dZ_{l-1} = (dZ_l * W_l^T) masked by A_l > 0     (b x d_in)
 // The last layer's logits are produced as split-K partial sums that the softmax
 // kernel adds in ascending split order, so every sum has a fixed order.
+//
+// The same sequence of launches also serves the whole round in one call
+// (easgd_mlp_round, steps (1)-(5)): Eq. (2) runs ahead of backward propagation
+// (on extra blocks of the first forward launch, on a second stream, or as a
+// kernel of its own), the input-gradient product of a layer runs before its
+// weight-gradient product, and that product applies the worker rule Eq. (1) /
+// Eq. (5),(6) to the layer's slice of every replica in its epilogue.
 #include "gemm_mfma.h"
 #include <mutex>
 

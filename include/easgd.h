@@ -184,8 +184,10 @@ typedef enum {
                                             3 = on extra blocks of the first forward product's launch; 1 = chosen per call
                                             (default): 3 when that launch leaves room on the chip, else 2 when P*N >= 2^24
                                             (below which ordering two streams costs more than it hides), else 0 */
-    EASGD_OPT_GEMM_XCD             = 6   /* 1 = the blocks of a matrix product are renumbered so that each of the eight dies
+    EASGD_OPT_GEMM_XCD             = 6,  /* 1 = the blocks of a matrix product are renumbered so that each of the eight dies
                                             works on whole workers (default), 0 = plain block order */
+    EASGD_OPT_GEMM_PAIR            = 7   /* 1 = independent products of backward propagation share a launch where their tile
+                                            shapes allow (default), 0 = one launch per product */
 } easgd_option;
 
 int easgd_set_option(int option, long value);

@@ -24,6 +24,7 @@ OPT_UPDATE_GROUPS = 3
 OPT_GEMM_TILE = 4
 OPT_ROUND_OVERLAP = 5
 OPT_GEMM_XCD = 6
+OPT_GEMM_PAIR = 7
 
 
 class EasgdError(RuntimeError):

@@ -25,6 +25,7 @@ struct Options {
     long gemm_tile = 0;
     long round_overlap = 1;
     long gemm_xcd = 1;
+    long gemm_pair = 1;
 };
 Options &options();
 

@@ -75,8 +75,19 @@ __device__ __forceinline__ f32x4 fetch4(const float *row, int idx0, int lim, int
     return v;
 }
 
+// LDS floats of one block of a tile configuration (both operands, two buffers each).
+template <int BM, int BN, int BK, int A_LAYOUT, int B_LAYOUT>
+constexpr int gemm_lds_floats()
+{
+    constexpr int PAD_K = (BK == 32) ? 1 : 2;
+    constexpr int PITCH_A = BM + (A_LAYOUT == K_CONTIG ? PAD_K : 4), PITCH_B = BN + (B_LAYOUT == K_CONTIG ? PAD_K : 4);
+    return 2 * BK * PITCH_A + 2 * BK * PITCH_B;
+}
+
+// The work of block `bid` of one product.  `lds` is the calling kernel's buffer of at least
+// gemm_lds_floats<...>() floats, 16-byte aligned: kernels that carry two products lend the same buffer to both.
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(GemmArgs p)
+__device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid, float *__restrict__ lds)
 {
     constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -92,22 +103,17 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
     constexpr int IT_A = (CHUNKS_A + NTHREADS - 1) / NTHREADS, IT_B = (CHUNKS_B + NTHREADS - 1) / NTHREADS;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 4 == 0, "tile shape");
 
-    __shared__ __attribute__((aligned(16))) float As[2][BK * PITCH_A];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK * PITCH_B];
+    float (*As)[BK * PITCH_A] = reinterpret_cast<float (*)[BK * PITCH_A]>(lds);
+    float (*Bs)[BK * PITCH_B] = reinterpret_cast<float (*)[BK * PITCH_B]>(lds + 2 * BK * PITCH_A);
+    static_assert((2 * BK * PITCH_A) % 4 == 0, "B tiles must stay 16-byte aligned");
 
     // block -> (worker, split, tile_m, tile_n)
     // Workgroups go to the eight accelerator dies (XCDs, each with its own L2) in turn, by block index.
     // With xcd_chunk > 0 the grid is a multiple of 8 and block b works on the logical index
     // (b % 8) * xcd_chunk + b / 8: each die then owns a run of consecutive tiles, i.e. whole workers,
     // so that an operand panel shared by the tiles of a worker is fetched into one L2 only.
-    if (p.ctr.blocks > 0 && blockIdx.x >= p.ctr.first_block) {         // uniform for the block
-        const size_t b = blockIdx.x - p.ctr.first_block;
-        if (p.ctr.vec) center_rule_block<f32x4>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
-        else center_rule_block<float>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
-        return;
-    }
     const int tiles = p.tiles_m * p.tiles_n;
-    int id = blockIdx.x;
+    int id = (int)bid;
     if (p.xcd_chunk > 0) {
         id = (id & 7) * p.xcd_chunk + (id >> 3);
         if (id >= tiles * p.splits * p.P) return;
@@ -501,6 +507,35 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
                 }
             }
     }
+}
+
+// One product per launch; the grid may be extended by blocks that run the center rule (p.ctr).
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(GemmArgs p)
+{
+    __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<BM, BN, BK, A_LAYOUT, B_LAYOUT>()];
+    if (p.ctr.blocks > 0 && blockIdx.x >= p.ctr.first_block) {         // uniform for the block
+        const size_t b = blockIdx.x - p.ctr.first_block;
+        if (p.ctr.vec) center_rule_block<f32x4>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
+        else center_rule_block<float>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
+        return;
+    }
+    gemm_block<BM, BN, BK, WAVES_M, WAVES_N, A_LAYOUT, B_LAYOUT, VEC, EPI>(p, blockIdx.x, lds);
+}
+
+// Two independent products in one launch: blocks [0, n0) work on p0 with the first configuration, the rest on
+// p1 with the second.  The products of backward propagation are short, so sharing a launch saves a launch
+// boundary and lets the blocks of one fill the wave slots and the tail the other leaves idle.  Both
+// configurations use 256 threads; the LDS buffer is the larger of the two needs.
+template <int BM0, int BN0, int BK0, int WM0, int WN0, int AL0, int BL0, bool VEC0, int EPI0,
+          int BM1, int BN1, int BK1, int WM1, int WN1, int AL1, int BL1, bool VEC1, int EPI1>
+__global__ __launch_bounds__(256, 2) void gemm_pair_kernel(GemmArgs p0, GemmArgs p1, unsigned n0)
+{
+    static_assert(WM0 * WN0 == 4 && WM1 * WN1 == 4, "both products use 256 threads");
+    constexpr int L0 = gemm_lds_floats<BM0, BN0, BK0, AL0, BL0>(), L1 = gemm_lds_floats<BM1, BN1, BK1, AL1, BL1>();
+    __shared__ __attribute__((aligned(16))) float lds[L0 > L1 ? L0 : L1];
+    if (blockIdx.x < n0) gemm_block<BM0, BN0, BK0, WM0, WN0, AL0, BL0, VEC0, EPI0>(p0, blockIdx.x, lds);
+    else gemm_block<BM1, BN1, BK1, WM1, WN1, AL1, BL1, VEC1, EPI1>(p1, blockIdx.x - n0, lds);
 }
 
 }  // namespace easgd

@@ -33,7 +33,7 @@ struct GradPlan {
     size_t N = 0;
     size_t off[MAX_LAYERS] = {0};       // packed offset of layer l
     size_t act_off[MAX_LAYERS] = {0};   // workspace offset (bytes) of A_l, l = 1..L-1
-    size_t logits_off = 0, rowloss_off = 0, dz_off[2] = {0, 0};
+    size_t logits_off = 0, rowloss_off = 0, dz_off[3] = {0, 0, 0};
     size_t bytes = 0;
     int splits = 1, k_per_split = 0;
     size_t center_off = 0, round_bytes = 0;
@@ -72,7 +72,7 @@ static bool make_plan(const int *dims, int L, int P, int b, GradPlan &pl)
     o += align_up((size_t)pl.splits * P * b * dims[L] * sizeof(float), 256);
     pl.rowloss_off = o;
     o += align_up((size_t)P * b * sizeof(float), 256);
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < 3; ++q) {
         pl.dz_off[q] = o;
         o += align_up((size_t)P * b * widest * sizeof(float), 256);
     }
@@ -148,10 +148,10 @@ __global__ __launch_bounds__(64) void mean_loss_kernel(const float *__restrict__
 
 enum Kind { FWD, DW, DA };
 
-template <int BM, int BN, int BK, int WM, int WN, int AL, int BL, int EPI>
-static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
+// Fills in the tile counts and the die-aware block numbering of a product; returns its number of blocks.
+template <int BM, int BN>
+static unsigned place_blocks(GemmArgs &a)
 {
-    GemmArgs a = a_in;
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (a.N + BN - 1) / BN;
     size_t total = (size_t)a.tiles_m * a.tiles_n * a.splits * a.P;
@@ -160,6 +160,36 @@ static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
         total = (total + 7) / 8 * 8;
         a.xcd_chunk = (int)(total / 8);
     }
+    return (unsigned)total;
+}
+
+// Two products of backward propagation in one launch (gemm_pair_kernel).
+// (i) the input-gradient product of layer l (64x64 tiles) with the weight-gradient product of a narrow layer
+//     l+1 (128x32 tile): the few blocks of the second fill wave slots the first leaves idle;
+// (ii) the weight-gradient products of two layers (64x64 tiles both): one launch boundary and one tail less.
+template <int EPI, bool VEC_DW>
+static void launch_pair_da_narrow_dw(GemmArgs da, GemmArgs dw, hipStream_t s)
+{
+    const unsigned n0 = place_blocks<64, 64>(da), n1 = place_blocks<128, 32>(dw);
+    hipLaunchKernelGGL((gemm_pair_kernel<64, 64, 32, 2, 2, K_CONTIG, K_CONTIG, true, EPI_MASK,
+                                         128, 32, SPLIT_BK, 4, 1, MN_CONTIG, MN_CONTIG, VEC_DW, EPI>),
+                       dim3(n0 + n1), dim3(256), 0, s, da, dw, n0);
+}
+
+template <int EPI>
+static void launch_pair_dw_dw(GemmArgs d0, GemmArgs d1, hipStream_t s)
+{
+    const unsigned n0 = place_blocks<64, 64>(d0), n1 = place_blocks<64, 64>(d1);
+    hipLaunchKernelGGL((gemm_pair_kernel<64, 64, 32, 2, 2, MN_CONTIG, MN_CONTIG, true, EPI,
+                                         64, 64, 32, 2, 2, MN_CONTIG, MN_CONTIG, true, EPI>),
+                       dim3(n0 + n1), dim3(256), 0, s, d0, d1, n0);
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int AL, int BL, int EPI>
+static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
+{
+    GemmArgs a = a_in;
+    size_t total = place_blocks<BM, BN>(a);
     static_assert(WM * WN * 64 == 256, "the center rule's extra blocks assume 256 threads");
     if (a.ctr.blocks > 0) {
         a.ctr.first_block = (unsigned)total;
@@ -320,7 +350,10 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     char *ws = static_cast<char *>(workspace);
     auto act = [&](int l) -> const float * { return l == 0 ? X : reinterpret_cast<const float *>(ws + pl.act_off[l]); };
     float *logits = reinterpret_cast<float *>(ws + pl.logits_off);
-    float *dz[2] = {reinterpret_cast<float *>(ws + pl.dz_off[0]), reinterpret_cast<float *>(ws + pl.dz_off[1])};
+    // dZ_l lives in buffer l % 3: the input-gradient product of layer l reads buffer l % 3 and writes (l-1) % 3
+    // while the weight-gradient product of layer l+1, which may share its launch, still reads (l+1) % 3
+    float *dz[3] = {reinterpret_cast<float *>(ws + pl.dz_off[0]), reinterpret_cast<float *>(ws + pl.dz_off[1]),
+                    reinterpret_cast<float *>(ws + pl.dz_off[2])};
     const bool base_vec = mult4(ld);
 
     // ---- Eq. (2); beside forward propagation when the second stream is in use ----
@@ -384,47 +417,89 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     }
     float *row_loss = reinterpret_cast<float *>(ws + pl.rowloss_off);
     const int rows = P * b;
-    hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) & 1], row_loss,
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) % 3], row_loss,
                        rows, b, dims[L], pl.splits, (size_t)rows * dims[L]);
     if (loss) hipLaunchKernelGGL(mean_loss_kernel, dim3(P), dim3(64), 0, s, row_loss, loss, b);
 
     // ---- backward propagation ----
+    // The weight-gradient product of a layer is held back until the next product is known, because two
+    // independent products can share a launch (launch_pair_*): with the input-gradient product of the layer
+    // below when the held one is narrow, or with the weight-gradient product of the layer below.
+    const int epi = !step ? EPI_NONE : (step->V ? EPI_ELASTIC_MOM : EPI_ELASTIC);
+    const bool pairing = options().gemm_pair != 0;
+    const bool tile64 = options().gemm_tile == 0 || options().gemm_tile == 2;   // wide backward products use 64x64
+    struct Held { bool have = false; GemmArgs a; bool vec = false; } held;
+    auto launch_dw = [&](const GemmArgs &d, bool vec) {
+        if (epi == EPI_NONE) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(d, vec, false, s);
+        else if (epi == EPI_ELASTIC) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC>(d, vec, false, s);
+        else launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM>(d, vec, false, s);
+    };
+    auto flush = [&]() {
+        if (held.have) launch_dw(held.a, held.vec);
+        held.have = false;
+    };
     for (int l = L - 1; l >= 0; --l) {
         const int d_in = dims[l], d_out = dims[l + 1];
-        const float *dz_l = dz[l & 1];
+        const float *dz_l = dz[l % 3];
         if (l > 0) {   // dZ_{l-1} = (dZ_l W_l^T) where A_l > 0
             GemmArgs a = {};
             a.A = dz_l; a.a_ws = (size_t)b * d_out; a.lda = d_out; a.a_lim = d_out; a.a_ones = -1;
             a.B = W + pl.off[l]; a.b_ws = ld; a.ldb = d_out;
-            a.C = dz[(l - 1) & 1]; a.c_ws = (size_t)b * d_in; a.ldc = d_in;
+            a.C = dz[(l - 1) % 3]; a.c_ws = (size_t)b * d_in; a.ldc = d_in;
             a.mask = act(l); a.mask_ws = (size_t)b * d_in; a.ldmask = d_in;
             a.M = b; a.N = d_in; a.K = d_out; a.P = P;
             a.splits = 1; a.k_per_split = (a.K + 63) / 64 * 64;
-            launch_gemm<K_CONTIG, K_CONTIG, EPI_MASK>(a, base_vec && mult4(d_out) && mult4(pl.off[l]), false, s);
-        }
-        {   // [dW_l ; db_l] = [A_l 1]^T dZ_l, stored at the layer's place in the packed gradient
-            GemmArgs a = {};
-            a.A = act(l); a.a_ws = (size_t)b * d_in; a.lda = d_in; a.a_lim = d_in; a.a_ones = d_in;
-            a.B = dz_l; a.b_ws = (size_t)b * d_out; a.ldb = d_out;
-            a.C = G ? G + pl.off[l] : nullptr; a.c_ws = ld; a.ldc = d_out;
-            a.M = d_in + 1; a.N = d_out; a.K = b; a.P = P;
-            a.splits = 1; a.k_per_split = (a.K + 63) / 64 * 64;
-            const bool vec = mult4(d_in) && mult4(d_out);
-            if (!step) {
-                launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, false, s);
+            const bool vec = base_vec && mult4(d_out) && mult4(pl.off[l]);
+            // sharing costs the input-gradient blocks some occupancy (the kernel takes the larger register count
+            // of its two halves), so it is done only when their launch leaves wave slots idle anyway
+            const bool room = (size_t)((a.M + 63) / 64) * ((a.N + 63) / 64) * P <= (size_t)3 * num_cus();
+            if (held.have && pairing && held.a.N <= 32 && vec && tile64 && a.N > 32 && room) {
+                if (epi == EPI_NONE) {
+                    if (held.vec) launch_pair_da_narrow_dw<EPI_NONE, true>(a, held.a, s);
+                    else launch_pair_da_narrow_dw<EPI_NONE, false>(a, held.a, s);
+                } else if (epi == EPI_ELASTIC) {
+                    if (held.vec) launch_pair_da_narrow_dw<EPI_ELASTIC, true>(a, held.a, s);
+                    else launch_pair_da_narrow_dw<EPI_ELASTIC, false>(a, held.a, s);
+                } else {
+                    if (held.vec) launch_pair_da_narrow_dw<EPI_ELASTIC_MOM, true>(a, held.a, s);
+                    else launch_pair_da_narrow_dw<EPI_ELASTIC_MOM, false>(a, held.a, s);
+                }
+                held.have = false;
             } else {
-                // the first kernel that changes W waits for the center rule, which reads W at time t
-                if (lane && l == L - 1 && hipStreamWaitEvent(s, lane->join, 0) != hipSuccess)
-                    return fail(EASGD_ELAUNCH, "%s: stream join failed", name);
-                a.Wt = step->W + pl.off[l];
-                a.Vt = step->V ? step->V + pl.off[l] : nullptr;
-                a.center = old_center + pl.off[l];
-                a.eta = step->eta; a.rho = step->rho; a.alpha = step->eta * step->rho; a.delta = step->delta;
-                if (step->V) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM>(a, vec, false, s);
-                else launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC>(a, vec, false, s);
+                flush();
+                launch_gemm<K_CONTIG, K_CONTIG, EPI_MASK>(a, vec, false, s);
             }
         }
+        // the first kernel that changes W waits for the center rule, which reads W at time t
+        if (step && lane && l == L - 1 && hipStreamWaitEvent(s, lane->join, 0) != hipSuccess)
+            return fail(EASGD_ELAUNCH, "%s: stream join failed", name);
+        // [dW_l ; db_l] = [A_l 1]^T dZ_l, stored at the layer's place in the packed gradient
+        GemmArgs d = {};
+        d.A = act(l); d.a_ws = (size_t)b * d_in; d.lda = d_in; d.a_lim = d_in; d.a_ones = d_in;
+        d.B = dz_l; d.b_ws = (size_t)b * d_out; d.ldb = d_out;
+        d.C = G ? G + pl.off[l] : nullptr; d.c_ws = ld; d.ldc = d_out;
+        d.M = d_in + 1; d.N = d_out; d.K = b; d.P = P;
+        d.splits = 1; d.k_per_split = (d.K + 63) / 64 * 64;
+        if (step) {
+            d.Wt = step->W + pl.off[l];
+            d.Vt = step->V ? step->V + pl.off[l] : nullptr;
+            d.center = old_center + pl.off[l];
+            d.eta = step->eta; d.rho = step->rho; d.alpha = step->eta * step->rho; d.delta = step->delta;
+        }
+        const bool vec = mult4(d_in) && mult4(d_out);
+        if (held.have) {     // two weight-gradient products in a row (no input-gradient product for layer 0)
+            if (pairing && tile64 && held.vec && vec && held.a.N > 32 && d.N > 32) {
+                if (epi == EPI_NONE) launch_pair_dw_dw<EPI_NONE>(held.a, d, s);
+                else if (epi == EPI_ELASTIC) launch_pair_dw_dw<EPI_ELASTIC>(held.a, d, s);
+                else launch_pair_dw_dw<EPI_ELASTIC_MOM>(held.a, d, s);
+                held.have = false;
+                continue;
+            }
+            flush();
+        }
+        held.have = true; held.a = d; held.vec = vec;
     }
+    flush();
     return check_launch(name);
 }
 

@@ -73,6 +73,10 @@ int easgd_set_option(int option, long value)
         if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "gemm xcd must be 0 or 1, got %ld", value);
         o.gemm_xcd = value;
         return EASGD_OK;
+    case EASGD_OPT_GEMM_PAIR:
+        if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "gemm pair must be 0 or 1, got %ld", value);
+        o.gemm_pair = value;
+        return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
     }
@@ -88,6 +92,7 @@ long easgd_get_option(int option)
     case EASGD_OPT_GEMM_TILE: return o.gemm_tile;
     case EASGD_OPT_ROUND_OVERLAP: return o.round_overlap;
     case EASGD_OPT_GEMM_XCD: return o.gemm_xcd;
+    case EASGD_OPT_GEMM_PAIR: return o.gemm_pair;
     default: return -1;
     }
 }

@@ -193,3 +193,34 @@ def test_round_can_be_captured_in_a_hip_graph(hip, overlap):
             torch.cuda.synchronize()
     finally:
         hip.set_option(hip.OPT_ROUND_OVERLAP, old)
+
+
+@pytest.mark.parametrize("dims,P,b", [((784, 256, 128, 10), 3, 100), ((300, 260, 10), 5, 64), ((128, 200, 136, 64, 12), 4, 37),
+                                      ((130, 96, 1000), 2, 9), ((512, 384, 10), 40, 128)],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_shared_launches_change_nothing(hip, dims, P, b):
+    """Independent products of backward propagation may share a launch (the narrow last layer's weight gradient
+    with the input gradient below it, the weight gradients of two layers); every block still does exactly the work
+    it does in a launch of its own, so gradients and rounds are the same bits with the sharing on and off."""
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=35)
+    dX, dy = to_dev(X), to_dev(y)
+    old = hip.get_option(hip.OPT_GEMM_PAIR)
+    out = []
+    try:
+        for pair in (0, 1):
+            hip.set_option(hip.OPT_GEMM_PAIR, pair)
+            res = []
+            for momentum in (False, True):
+                fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
+                fG = torch.full_like(fW, float("nan"))
+                hip.easgd_mlp_round(dims, fW, fWc, dX, dy, ETA, RHO, V=fV if momentum else None, delta=DELTA, G=fG)
+                res += [to_host(fW), to_host(fV), to_host(fWc), to_host(fG)]
+            gW = to_dev(W); gG = torch.full_like(gW, float("nan"))
+            hip.easgd_grad(dims, gW, dX, dy, gG)
+            res.append(to_host(gG))
+            out.append(res)
+    finally:
+        hip.set_option(hip.OPT_GEMM_PAIR, old)
+    for a, c in zip(out[0], out[1]):
+        np.testing.assert_array_equal(a, c)
+    np.testing.assert_array_equal(out[0][3], out[0][-1])      # the round's stored gradient is easgd_grad's

@@ -343,6 +343,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--round-overlap", type=int, default=None, choices=(0, 1, 2, 3),
                     help="library option EASGD_OPT_ROUND_OVERLAP for the one-call path (default: the library's)")
+    ap.add_argument("--gemm-pair", type=int, default=None, choices=(0, 1),
+                    help="library option EASGD_OPT_GEMM_PAIR: 0 = one launch per matrix product (tells the products "
+                         "apart in a profile), default: the library's (shared launches)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P replicas live in one HBM); --gpus must be 1. "
@@ -356,6 +359,8 @@ def main():
 
     if args.round_overlap is not None:
         hip.set_option(hip.OPT_ROUND_OVERLAP, args.round_overlap)
+    if args.gemm_pair is not None:
+        hip.set_option(hip.OPT_GEMM_PAIR, args.gemm_pair)
     wl = workloads.WORKLOADS[args.workload]
     steps = args.steps if args.steps is not None else (300 if wl.has_grad else 100)
     warmup = args.warmup if args.warmup is not None else (20 if wl.has_grad else 5)

@@ -39,7 +39,10 @@ struct GradPlan {
     size_t center_off = 0, round_bytes = 0;
 };
 
-static constexpr int SPLIT_BK = 16;     // slab depth of the kernel that produces the logits
+// Slab depth of the 128x32 tile (logits, narrow weight gradients).  These products are latency-bound: a block has
+// a handful of slabs and little to multiply per slab, so fewer, deeper slabs win (32 against 16: logits 26 -> 19 us
+// at 2048 inputs, 16.7 -> 14 us at 1024).
+static constexpr int SPLIT_BK = 32;
 
 static bool make_plan(const int *dims, int L, int P, int b, GradPlan &pl)
 {

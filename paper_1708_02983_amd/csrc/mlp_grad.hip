@@ -40,8 +40,8 @@ struct GradPlan {
 };
 
 // Slab depth of the 128x32 tile (logits, narrow weight gradients).  These products are latency-bound: a block has
-// a handful of slabs and little to multiply per slab, so fewer, deeper slabs win (32 against 16: logits 26 -> 19 us
-// at 2048 inputs, 16.7 -> 14 us at 1024).
+// a handful of slabs and little to multiply per slab, so fewer, deeper slabs win (32 against 16: the logits of a
+// 2048-wide layer 26 -> 19 us, a whole 784-10 round 25.8 -> 23.2 us).
 static constexpr int SPLIT_BK = 32;
 
 static bool make_plan(const int *dims, int L, int P, int b, GradPlan &pl)

@@ -346,6 +346,9 @@ def main():
     ap.add_argument("--gemm-pair", type=int, default=None, choices=(0, 1),
                     help="library option EASGD_OPT_GEMM_PAIR: 0 = one launch per matrix product (tells the products "
                          "apart in a profile), default: the library's (shared launches)")
+    ap.add_argument("--mlp-head", type=int, default=None, choices=(0, 1),
+                    help="library option EASGD_OPT_MLP_HEAD: 0 = the last layer as three launches, default: the "
+                         "library's (one launch for a narrow last layer)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P replicas live in one HBM); --gpus must be 1. "
@@ -361,6 +364,8 @@ def main():
         hip.set_option(hip.OPT_ROUND_OVERLAP, args.round_overlap)
     if args.gemm_pair is not None:
         hip.set_option(hip.OPT_GEMM_PAIR, args.gemm_pair)
+    if args.mlp_head is not None:
+        hip.set_option(hip.OPT_MLP_HEAD, args.mlp_head)
     wl = workloads.WORKLOADS[args.workload]
     steps = args.steps if args.steps is not None else (300 if wl.has_grad else 100)
     warmup = args.warmup if args.warmup is not None else (20 if wl.has_grad else 5)

@@ -25,6 +25,7 @@ OPT_GEMM_TILE = 4
 OPT_ROUND_OVERLAP = 5
 OPT_GEMM_XCD = 6
 OPT_GEMM_PAIR = 7
+OPT_MLP_HEAD = 8
 
 
 class EasgdError(RuntimeError):

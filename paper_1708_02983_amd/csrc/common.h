@@ -26,6 +26,7 @@ struct Options {
     long round_overlap = 1;
     long gemm_xcd = 1;
     long gemm_pair = 1;
+    long mlp_head = 1;
 };
 Options &options();
 

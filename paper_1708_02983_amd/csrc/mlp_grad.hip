@@ -10,7 +10,9 @@
 //   weights   [dW;db]  = [A_l 1]^T * dZ_l                     ((d_in+1) x d_out, contiguous in G)
 //   inputs    dZ_{l-1} = (dZ_l * W_l^T) masked by A_l > 0     (b x d_in)
 // The last layer's logits are produced as split-K partial sums that the softmax
-// kernel adds in ascending split order, so every sum has a fixed order.
+// kernel adds in ascending split order, so every sum has a fixed order; a last
+// layer of at most 16 classes below a hidden layer instead takes one launch for
+// its forward product, the softmax and its input-gradient product (mlp_head_kernel).
 //
 // The same sequence of launches also serves the whole round in one call
 // (easgd_mlp_round, steps (1)-(5)): Eq. (2) runs ahead of backward propagation
@@ -145,6 +147,214 @@ __global__ __launch_bounds__(64) void mean_loss_kernel(const float *__restrict__
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
     if (lane == 0) loss[w] = acc / (float)b;
+}
+
+// ---- the head of the network in one launch ---------------------------------
+// With few classes the last layer is latency-bound however it is tiled: its logits product has only P*b*C outputs
+// with a long K, and the input-gradient product that follows has K = C.  For C <= HEAD_MAX_C this kernel does
+// the last layer's forward product, the softmax cross-entropy and the last layer's input-gradient product
+// (Section 2.2) for HEAD_ROWS sample rows of one worker per block.  Thread t owns the columns n = t, t+256, ...
+// of the layer input: it loads rows n of W_L (C values each) and A[r][n] of the block's rows once, into
+// registers, and uses them for both products:
+//   z[r][c]  = sum_n A[r][n] W_L[n][c] + b_L[c]   per thread ascending n, then a fixed exchange tree over the
+//                                                  lanes, then the four wavefronts in ascending order, then b_L
+//   dz[r][c] = (softmax(z[r])[c] - [c == y_r]) / b,   row_loss[r] = -log softmax(z[r])[y_r]
+//   da[r][n] = sum_c dz[r][c] W_L[n][c] (ascending c), zero where A[r][n] <= 0
+// Blocks are numbered worker-fastest, so that with P a multiple of 8 all blocks of a worker run on one die and
+// share its copy of W_L in that die's L2.
+static constexpr int HEAD_MAX_C = 16;
+static constexpr int HEAD_ROWS = 4;
+
+struct HeadArgs {
+    const float *A;         // A_{L-1}: [P][b][d_in]
+    const float *Wl;        // [W_L ; b_L] of worker 0: (d_in+1) x C row-major; worker stride w_ws elements
+    const int *y;           // [P*b] labels
+    float *dz;              // [P*b][C]
+    float *row_loss;        // [P*b]
+    float *da;              // dZ_{L-2}: [P][b][d_in]
+    size_t w_ws;
+    int d_in, C, b, P;
+};
+
+// Partials a lane holds before step `step` of the exchange tree that starts from n per lane.
+static constexpr int head_tree_count(int n, int step)
+{
+    for (int q = 0; q < step; ++q)
+        if (n % 2 == 0) n /= 2;
+    return n;
+}
+
+// Steps STEP..5 of the exchange tree on the first CNT entries of v (see mlp_head_kernel).
+template <int N, int CNT, int STEP>
+__device__ __forceinline__ void head_tree(float (&v)[N], int lane, int &base, bool &writer)
+{
+    if constexpr (STEP < 6) {
+        constexpr int m = 32 >> STEP;
+        const bool up = (lane & m) != 0;
+        if constexpr (CNT % 2 == 0) {
+            constexpr int half = CNT / 2;
+#pragma unroll
+            for (int i = 0; i < half; ++i) {
+                const float keep = up ? v[i + half] : v[i];
+                const float send = up ? v[i] : v[i + half];
+                v[i] = keep + __shfl_xor(send, m);
+            }
+            base += up ? half : 0;
+            head_tree<N, half, STEP + 1>(v, lane, base, writer);
+        } else {
+#pragma unroll
+            for (int i = 0; i < CNT; ++i) v[i] += __shfl_xor(v[i], m);
+            writer = writer && !up;
+            head_tree<N, CNT, STEP + 1>(v, lane, base, writer);
+        }
+    }
+}
+
+// CP: class count rounded up to a multiple of 4; ONE_PASS: d_in <= 1024, every thread keeps its operands in
+// registers between the two products instead of loading them again.
+template <int ROWS, int CP, bool ONE_PASS>
+__global__ __launch_bounds__(256) void mlp_head_kernel(HeadArgs h)
+{
+    constexpr int NT = 4;                    // columns per thread and pass
+    constexpr int CNT = ROWS * CP;           // partial logits per thread
+    __shared__ float part[4][CNT];
+    __shared__ float dzs[ROWS][CP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int w = blockIdx.x % h.P;
+    const int r0 = (blockIdx.x / h.P) * ROWS;
+    const int C = h.C, K = h.d_in;
+    const int rows_here = min(ROWS, h.b - r0);
+    const float *__restrict__ Wg = h.Wl + (size_t)w * h.w_ws;
+    const float *__restrict__ Am = h.A + ((size_t)w * h.b + r0) * (size_t)K;
+
+    float wv[NT][CP], gate[ROWS][NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+#pragma unroll
+        for (int c = 0; c < CP; ++c) wv[j][c] = 0.f;
+#pragma unroll
+        for (int rr = 0; rr < ROWS; ++rr) gate[rr][j] = 0.f;
+    }
+    auto load = [&](int n0) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int n = n0 + 256 * j;
+            const bool ok = n < K;
+#pragma unroll
+            for (int rr = 0; rr < ROWS; ++rr) gate[rr][j] = (ok && rr < rows_here) ? Am[(size_t)rr * K + n] : 0.f;
+#pragma unroll
+            for (int c = 0; c < CP; ++c) wv[j][c] = (ok && c < C) ? Wg[(size_t)n * C + c] : 0.f;
+        }
+    };
+
+    // partial logits of the thread's columns
+    float v[CNT];
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) v[i] = 0.f;
+    for (int n0 = tid; n0 < K; n0 += 256 * NT) {
+        load(n0);
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int rr = 0; rr < ROWS; ++rr)
+#pragma unroll
+                for (int c = 0; c < CP; ++c) v[rr * CP + c] = fmaf(gate[rr][j], wv[j][c], v[rr * CP + c]);
+    }
+    // exchange tree over the lanes, partner distance 32, 16, ..., 1: while a lane's count of partials is even it
+    // keeps one half of them and receives the partner's sums of the same half; once it is odd, both partners add
+    // the other's partials to all of theirs.  Each partial ends up summed over the 64 lanes in a fixed order.
+    {
+        int base = 0;
+        bool writer = true;
+        head_tree<CNT, CNT, 0>(v, lane, base, writer);
+        if (writer) {
+#pragma unroll
+            for (int i = 0; i < head_tree_count(CNT, 6); ++i) part[wave][base + i] = v[i];
+        }
+    }
+    __syncthreads();
+
+    // softmax cross-entropy: one thread per sample row
+    if (tid < ROWS) {
+        const int rr = tid;
+        float d[CP];
+#pragma unroll
+        for (int c = 0; c < CP; ++c) d[c] = 0.f;
+        if (rr < rows_here) {
+            const size_t grow = (size_t)w * h.b + r0 + rr;
+            const int label = h.y[grow];
+            float z[CP];
+            float zmax = -INFINITY;
+#pragma unroll
+            for (int c = 0; c < CP; ++c)
+                if (c < C) {
+                    const int i = rr * CP + c;
+                    z[c] = (((part[0][i] + part[1][i]) + part[2][i]) + part[3][i]) + Wg[(size_t)K * C + c];
+                    zmax = fmaxf(zmax, z[c]);
+                }
+            float sum = 0.f, zlabel = 0.f;
+#pragma unroll
+            for (int c = 0; c < CP; ++c)
+                if (c < C) {
+                    if (c == label) zlabel = z[c] - zmax;
+                    z[c] = expf(z[c] - zmax);
+                    sum += z[c];
+                }
+            const float inv_sum = 1.0f / sum, inv_b = 1.0f / (float)h.b;
+#pragma unroll
+            for (int c = 0; c < CP; ++c)
+                if (c < C) {
+                    d[c] = (z[c] * inv_sum - (c == label ? 1.f : 0.f)) * inv_b;
+                    h.dz[grow * (size_t)C + c] = d[c];
+                }
+            h.row_loss[grow] = logf(sum) - zlabel;
+        }
+#pragma unroll
+        for (int c = 0; c < CP; ++c) dzs[rr][c] = d[c];
+    }
+    if (!h.da) return;                                                         // uniform
+    __syncthreads();
+
+    // input gradient of the last layer for the block's rows
+    float *__restrict__ da = h.da + ((size_t)w * h.b + r0) * (size_t)K;
+    for (int n0 = tid; n0 < K; n0 += 256 * NT) {
+        if (!ONE_PASS) load(n0);
+#pragma unroll
+        for (int rr = 0; rr < ROWS; ++rr) {
+            if (rr < rows_here) {
+                float d[CP];
+#pragma unroll
+                for (int c = 0; c < CP; ++c) d[c] = dzs[rr][c];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int n = n0 + 256 * j;
+                    float o = 0.f;
+#pragma unroll
+                    for (int c = 0; c < CP; ++c) o = fmaf(d[c], wv[j][c], o);
+                    if (n < K) da[(size_t)rr * K + n] = gate[rr][j] > 0.f ? o : 0.f;
+                }
+            }
+        }
+    }
+}
+
+// Whether the head of a network with these layer widths takes the single-launch path.
+static bool head_fits(const int *dims, int L) { return L >= 2 && dims[L] <= HEAD_MAX_C; }
+
+template <int CP>
+static void launch_head_cp(const HeadArgs &h, unsigned blocks, hipStream_t s)
+{
+    if (h.d_in <= 1024) hipLaunchKernelGGL((mlp_head_kernel<HEAD_ROWS, CP, true>), dim3(blocks), dim3(256), 0, s, h);
+    else hipLaunchKernelGGL((mlp_head_kernel<HEAD_ROWS, CP, false>), dim3(blocks), dim3(256), 0, s, h);
+}
+
+static void launch_head(const HeadArgs &h, hipStream_t s)
+{
+    const unsigned blocks = (unsigned)h.P * (unsigned)((h.b + HEAD_ROWS - 1) / HEAD_ROWS);
+    if (h.C <= 4) launch_head_cp<4>(h, blocks, s);
+    else if (h.C <= 8) launch_head_cp<8>(h, blocks, s);
+    else if (h.C <= 12) launch_head_cp<12>(h, blocks, s);
+    else launch_head_cp<16>(h, blocks, s);
 }
 
 // ---- GEMM dispatch -------------------------------------------------------
@@ -395,7 +605,9 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     }
 
     // ---- forward propagation ----
-    for (int l = 0; l < L; ++l) {
+    // a narrow last layer goes through mlp_head_kernel together with the softmax and its own input gradient
+    const bool head = options().mlp_head != 0 && head_fits(dims, L);
+    for (int l = 0; l < (head ? L - 1 : L); ++l) {
         const int d_in = dims[l], d_out = dims[l + 1];
         const bool last = (l == L - 1);
         GemmArgs a = {};
@@ -420,8 +632,17 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     }
     float *row_loss = reinterpret_cast<float *>(ws + pl.rowloss_off);
     const int rows = P * b;
-    hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) % 3], row_loss,
-                       rows, b, dims[L], pl.splits, (size_t)rows * dims[L]);
+    if (head) {
+        HeadArgs h = {};
+        h.A = act(L - 1); h.Wl = W + pl.off[L - 1]; h.w_ws = ld; h.y = y;
+        h.dz = dz[(L - 1) % 3]; h.row_loss = row_loss; h.da = dz[(L - 2) % 3];
+        h.d_in = dims[L - 1]; h.C = dims[L]; h.b = b; h.P = P;
+        if ((size_t)P * ((b + HEAD_ROWS - 1) / HEAD_ROWS) > 0x7fffffffull) return fail(EASGD_ERANGE, "%s: P*b too large", name);
+        launch_head(h, s);
+    } else {
+        hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) % 3], row_loss,
+                           rows, b, dims[L], pl.splits, (size_t)rows * dims[L]);
+    }
     if (loss) hipLaunchKernelGGL(mean_loss_kernel, dim3(P), dim3(64), 0, s, row_loss, loss, b);
 
     // ---- backward propagation ----
@@ -444,7 +665,7 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     for (int l = L - 1; l >= 0; --l) {
         const int d_in = dims[l], d_out = dims[l + 1];
         const float *dz_l = dz[l % 3];
-        if (l > 0) {   // dZ_{l-1} = (dZ_l W_l^T) where A_l > 0
+        if (l > 0 && !(head && l == L - 1)) {   // dZ_{l-1} = (dZ_l W_l^T) where A_l > 0
             GemmArgs a = {};
             a.A = dz_l; a.a_ws = (size_t)b * d_out; a.lda = d_out; a.a_lim = d_out; a.a_ones = -1;
             a.B = W + pl.off[l]; a.b_ws = ld; a.ldb = d_out;

@@ -77,6 +77,10 @@ int easgd_set_option(int option, long value)
         if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "gemm pair must be 0 or 1, got %ld", value);
         o.gemm_pair = value;
         return EASGD_OK;
+    case EASGD_OPT_MLP_HEAD:
+        if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "mlp head must be 0 or 1, got %ld", value);
+        o.mlp_head = value;
+        return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
     }
@@ -93,6 +97,7 @@ long easgd_get_option(int option)
     case EASGD_OPT_ROUND_OVERLAP: return o.round_overlap;
     case EASGD_OPT_GEMM_XCD: return o.gemm_xcd;
     case EASGD_OPT_GEMM_PAIR: return o.gemm_pair;
+    case EASGD_OPT_MLP_HEAD: return o.mlp_head;
     default: return -1;
     }
 }

@@ -105,4 +105,6 @@ def test_options_roundtrip(lib):
     assert lib.easgd_set_option(6, 0) == 0 and lib.easgd_get_option(6) == 0 and lib.easgd_set_option(6, 1) == 0
     assert lib.easgd_get_option(4) == 0 and lib.easgd_set_option(4, 4) == -1
     assert lib.easgd_get_option(7) == 1 and lib.easgd_set_option(7, 2) == -1 and lib.easgd_set_option(7, 1) == 0
+    assert lib.easgd_get_option(8) == 1 and lib.easgd_set_option(8, 2) == -1
+    assert lib.easgd_set_option(8, 0) == 0 and lib.easgd_get_option(8) == 0 and lib.easgd_set_option(8, 1) == 0
     assert lib.easgd_version() >= 100

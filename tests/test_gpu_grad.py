@@ -124,3 +124,46 @@ def test_every_tile_shape_gives_the_same_gradient(hip, tile):
     for i in range(P):
         _, loss_ref, _ = match_gradient(G[i], dims, W[i], X[i], y[i], PER_ROUND_TOL)
         assert abs(loss[i] - loss_ref) <= 1e-5 * abs(loss_ref)
+
+
+# Last layers that take the single-launch head (at most 16 classes below a hidden layer) and ones that do not:
+# one class; 16 and 17 classes; widths that are no multiple of 4 or of the 256 columns the threads of a block
+# cover; hidden layers wider than one pass of 1024 columns (one, two and several passes); a single row and a
+# ragged last row group per worker.
+HEAD_CASES = [
+    ((12, 9, 1), 2, 5),
+    ((40, 64, 16), 3, 8),
+    ((40, 64, 17), 3, 8),
+    ((31, 1027, 10), 2, 9),
+    ((64, 2050, 7), 2, 1),
+    ((16, 3000, 10), 2, 19),
+    ((16, 3300, 10), 1, 4),
+    ((20, 1024, 12), 8, 16),
+    ((20, 1025, 5), 9, 17),
+]
+
+
+@pytest.mark.parametrize("dims,P,b", HEAD_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_head_of_the_network_in_one_launch_or_three(hip, dims, P, b):
+    """EASGD_OPT_MLP_HEAD only changes how the last layer is launched: both ways match the oracle."""
+    N, ld, W, X, y = _problem(dims, P, b, ld_pad=4)
+    G_ref, loss_ref = oracle.mlp_grad_all_workers(dims, W, X, y)
+    sl = oracle.layer_slices(dims)
+    old = hip.get_option(hip.OPT_MLP_HEAD)
+    got = {}
+    try:
+        for head in (1, 0):
+            hip.set_option(hip.OPT_MLP_HEAD, head)
+            G, loss = _run(hip, dims, W, X, y)
+            got[head] = G
+            assert np.isnan(G[:, N:]).all() and np.isfinite(G[:, :N]).all()
+            for i in range(P):
+                assert normwise(G[i], G_ref[i]) <= PER_ROUND_TOL
+                for w_sl, b_sl in sl:
+                    assert normwise(G[i, w_sl], G_ref[i, w_sl]) <= 2 * PER_ROUND_TOL
+                    assert normwise(G[i, b_sl], G_ref[i, b_sl]) <= 2 * PER_ROUND_TOL
+            np.testing.assert_allclose(loss, loss_ref, rtol=1e-5)
+    finally:
+        hip.set_option(hip.OPT_MLP_HEAD, old)
+    for i in range(P):
+        assert normwise(got[1][i], got[0][i]) <= PER_ROUND_TOL

@@ -188,9 +188,9 @@ typedef enum {
                                             works on whole workers (default), 0 = plain block order */
     EASGD_OPT_GEMM_PAIR            = 7,  /* 1 = independent products of backward propagation share a launch where their tile
                                             shapes allow (default), 0 = one launch per product */
-    EASGD_OPT_MLP_HEAD             = 8   /* 1 = a last layer of at most 16 classes that follows a hidden layer takes one launch
-                                            for its forward product, the softmax cross-entropy and its input-gradient product
-                                            (default), 0 = three launches (split-K product, softmax, product) */
+    EASGD_OPT_MLP_HEAD             = 8   /* 1 = a last layer of at most 16 classes takes one launch for its forward product, the
+                                            softmax cross-entropy and its input-gradient product (default), 0 = three launches
+                                            (split-K product, softmax, product) */
 } easgd_option;
 
 int easgd_set_option(int option, long value);

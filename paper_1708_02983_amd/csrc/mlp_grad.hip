@@ -11,8 +11,8 @@
 //   inputs    dZ_{l-1} = (dZ_l * W_l^T) masked by A_l > 0     (b x d_in)
 // The last layer's logits are produced as split-K partial sums that the softmax
 // kernel adds in ascending split order, so every sum has a fixed order; a last
-// layer of at most 16 classes below a hidden layer instead takes one launch for
-// its forward product, the softmax and its input-gradient product (mlp_head_kernel).
+// layer of at most 16 classes instead takes one launch for its forward product,
+// the softmax and its input-gradient product (mlp_head_kernel).
 //
 // The same sequence of launches also serves the whole round in one call
 // (easgd_mlp_round, steps (1)-(5)): Eq. (2) runs ahead of backward propagation
@@ -174,6 +174,7 @@ struct HeadArgs {
     float *da;              // dZ_{L-2}: [P][b][d_in]
     size_t w_ws;
     int d_in, C, b, P;
+    CenterJob ctr;          // optional extra blocks that run the center rule (single-layer networks)
 };
 
 // Partials a lane holds before step `step` of the exchange tree that starts from n per lane.
@@ -219,6 +220,12 @@ __global__ __launch_bounds__(256) void mlp_head_kernel(HeadArgs h)
     constexpr int CNT = ROWS * CP;           // partial logits per thread
     __shared__ float part[4][CNT];
     __shared__ float dzs[ROWS][CP];
+    if (h.ctr.blocks > 0 && blockIdx.x >= h.ctr.first_block) {         // uniform for the block
+        const size_t cb = blockIdx.x - h.ctr.first_block;
+        if (h.ctr.vec) center_rule_block<f32x4>(h.ctr.W, h.ctr.Wc, h.ctr.old, h.ctr.P, h.ctr.N, h.ctr.ld, h.ctr.alpha, cb, h.ctr.blocks, threadIdx.x);
+        else center_rule_block<float>(h.ctr.W, h.ctr.Wc, h.ctr.old, h.ctr.P, h.ctr.N, h.ctr.ld, h.ctr.alpha, cb, h.ctr.blocks, threadIdx.x);
+        return;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int w = blockIdx.x % h.P;
     const int r0 = (blockIdx.x / h.P) * ROWS;
@@ -339,7 +346,7 @@ __global__ __launch_bounds__(256) void mlp_head_kernel(HeadArgs h)
 }
 
 // Whether the head of a network with these layer widths takes the single-launch path.
-static bool head_fits(const int *dims, int L) { return L >= 2 && dims[L] <= HEAD_MAX_C; }
+static bool head_fits(const int *dims, int L) { return dims[L] <= HEAD_MAX_C; }
 
 template <int CP>
 static void launch_head_cp(const HeadArgs &h, unsigned blocks, hipStream_t s)
@@ -348,9 +355,15 @@ static void launch_head_cp(const HeadArgs &h, unsigned blocks, hipStream_t s)
     else hipLaunchKernelGGL((mlp_head_kernel<HEAD_ROWS, CP, false>), dim3(blocks), dim3(256), 0, s, h);
 }
 
-static void launch_head(const HeadArgs &h, hipStream_t s)
+static unsigned head_blocks(int P, int b) { return (unsigned)P * (unsigned)((b + HEAD_ROWS - 1) / HEAD_ROWS); }
+
+static void launch_head(HeadArgs h, hipStream_t s)
 {
-    const unsigned blocks = (unsigned)h.P * (unsigned)((h.b + HEAD_ROWS - 1) / HEAD_ROWS);
+    unsigned blocks = head_blocks(h.P, h.b);
+    if (h.ctr.blocks > 0) {
+        h.ctr.first_block = blocks;
+        blocks += h.ctr.blocks;
+    }
     if (h.C <= 4) launch_head_cp<4>(h, blocks, s);
     else if (h.C <= 8) launch_head_cp<8>(h, blocks, s);
     else if (h.C <= 12) launch_head_cp<12>(h, blocks, s);
@@ -569,6 +582,10 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
                     reinterpret_cast<float *>(ws + pl.dz_off[2])};
     const bool base_vec = mult4(ld);
 
+    // a narrow last layer goes through mlp_head_kernel together with the softmax and its own input gradient
+    const bool head = options().mlp_head != 0 && head_fits(dims, L);
+    if (head && (size_t)P * ((b + HEAD_ROWS - 1) / HEAD_ROWS) > 0x3fffffffull) return fail(EASGD_ERANGE, "%s: P*b too large", name);
+
     // ---- Eq. (2); beside forward propagation when the second stream is in use ----
     float *old_center = step ? reinterpret_cast<float *>(ws + pl.center_off) : nullptr;
     std::unique_lock<std::mutex> lane_guard;
@@ -582,7 +599,8 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         // enough to read to be worth the tens of microseconds that ordering two streams costs; else its own kernel.
         const long overlap = options().round_overlap;
         const int splits0 = (L == 1) ? pl.splits : 1;
-        const bool room = forward_launch_has_room(b, dims[1], P, splits0);
+        const bool room = (head && L == 1) ? head_blocks(P, b) <= 3u * (unsigned)num_cus()
+                                           : forward_launch_has_room(b, dims[1], P, splits0);
         attach_center = (overlap == 3) || (overlap == 1 && room);
         if (!attach_center && (overlap == 2 || (overlap == 1 && (size_t)P * pl.N >= ((size_t)1 << 24)))) {
             lane_guard = std::unique_lock<std::mutex>(side_mutex);
@@ -605,8 +623,15 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     }
 
     // ---- forward propagation ----
-    // a narrow last layer goes through mlp_head_kernel together with the softmax and its own input gradient
-    const bool head = options().mlp_head != 0 && head_fits(dims, L);
+    CenterJob center_job = {};           // rides on the first launch of forward propagation when attach_center
+    if (attach_center) {
+        const bool cvec = aligned16(step->W) && aligned16(step->Wc) && aligned16(old_center) && (ld % 4 == 0);
+        const size_t cblocks = (cvec ? pl.N / 4 : pl.N) / 256 + 1;
+        if (cblocks > 0x3fffffffu) return fail(EASGD_ERANGE, "%s: N too large", name);
+        center_job.W = step->W; center_job.Wc = step->Wc; center_job.old = old_center;
+        center_job.N = pl.N; center_job.ld = ld; center_job.P = P; center_job.vec = cvec ? 1 : 0;
+        center_job.alpha = step->eta * step->rho; center_job.blocks = (unsigned)cblocks;
+    }
     for (int l = 0; l < (head ? L - 1 : L); ++l) {
         const int d_in = dims[l], d_out = dims[l + 1];
         const bool last = (l == L - 1);
@@ -618,14 +643,7 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         a.splits = last ? pl.splits : 1;
         a.k_per_split = last ? pl.k_per_split : ((a.K + 63) / 64 * 64);
         a.c_ss = (size_t)P * b * d_out;
-        if (attach_center && l == 0) {
-            const bool cvec = aligned16(step->W) && aligned16(step->Wc) && aligned16(old_center) && (ld % 4 == 0);
-            const size_t cblocks = (cvec ? pl.N / 4 : pl.N) / 256 + 1;
-            if (cblocks > 0x3fffffffu) return fail(EASGD_ERANGE, "%s: N too large", name);
-            a.ctr.W = step->W; a.ctr.Wc = step->Wc; a.ctr.old = old_center;
-            a.ctr.N = pl.N; a.ctr.ld = ld; a.ctr.P = P; a.ctr.vec = cvec ? 1 : 0;
-            a.ctr.alpha = step->eta * step->rho; a.ctr.blocks = (unsigned)cblocks;
-        }
+        if (l == 0) a.ctr = center_job;
         const bool vec = base_vec && mult4(d_in) && mult4(d_out) && mult4(pl.off[l]);
         if (last) launch_gemm<K_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, true, s);
         else launch_gemm<K_CONTIG, MN_CONTIG, EPI_RELU>(a, vec, true, s);
@@ -635,9 +653,9 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     if (head) {
         HeadArgs h = {};
         h.A = act(L - 1); h.Wl = W + pl.off[L - 1]; h.w_ws = ld; h.y = y;
-        h.dz = dz[(L - 1) % 3]; h.row_loss = row_loss; h.da = dz[(L - 2) % 3];
+        h.dz = dz[(L - 1) % 3]; h.row_loss = row_loss; h.da = L >= 2 ? dz[(L - 2) % 3] : nullptr;
         h.d_in = dims[L - 1]; h.C = dims[L]; h.b = b; h.P = P;
-        if ((size_t)P * ((b + HEAD_ROWS - 1) / HEAD_ROWS) > 0x7fffffffull) return fail(EASGD_ERANGE, "%s: P*b too large", name);
+        if (L == 1) h.ctr = center_job;
         launch_head(h, s);
     } else {
         hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) % 3], row_loss,

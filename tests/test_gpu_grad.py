@@ -126,11 +126,13 @@ def test_every_tile_shape_gives_the_same_gradient(hip, tile):
         assert abs(loss[i] - loss_ref) <= 1e-5 * abs(loss_ref)
 
 
-# Last layers that take the single-launch head (at most 16 classes below a hidden layer) and ones that do not:
+# Last layers that take the single-launch head (at most 16 classes) and ones that do not; a single-layer network;
 # one class; 16 and 17 classes; widths that are no multiple of 4 or of the 256 columns the threads of a block
 # cover; hidden layers wider than one pass of 1024 columns (one, two and several passes); a single row and a
 # ragged last row group per worker.
 HEAD_CASES = [
+    ((784, 10), 4, 64),
+    ((300, 3), 2, 7),
     ((12, 9, 1), 2, 5),
     ((40, 64, 16), 3, 8),
     ((40, 64, 17), 3, 8),

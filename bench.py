@@ -255,6 +255,13 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+# HBM bytes per easgd_grad launch (all its kernels), measured the same way; see profiles/easgd_grad_cfg2_hbm_traffic.md.
+# Keyed by workload name.
+MEASURED_GRAD_TRAFFIC_BYTES = {
+    "cfg2": 131_933.3 * 1024 * 2.000 + 149_345.8 * 1024 * 1.000,
+}
+
+
 def hbm_roofline(wl, update_ms, ceiling_gbs=None):
     achieved = update_bytes(wl) / (update_ms * 1e-3) / 1e9
     out = {"bound": "hbm", "kernel": "elastic_vec4_kernel (measgd)" if wl.momentum else "elastic_vec4_kernel (easgd)",
@@ -388,7 +395,8 @@ def main():
                                                      "elastic_update": round(r["update_ms"], 4)}}})
         line["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all products of easgd_grad, two-call path)",
                             "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                            "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
+                            "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4),
+                            "traffic": MEASURED_GRAD_TRAFFIC_BYTES.get(args.workload),
                             "useful_flops_per_launch": grad_flops(wl), "avg_launch_ms": round(r["grad_ms"], 4)}
         line["host_fed"] = bench_host_fed(hip, wl, steps, warmup)
         line["update_in_round"] = {"GBs_algorithmic": round(update_bytes(wl) / (r["update_ms"] * 1e-3) / 1e9, 1),

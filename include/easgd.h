@@ -155,6 +155,11 @@ int easgd_grad(const int *dims, int n_layers,
  *   delta is ignored when V == NULL; the other arguments are those of easgd_grad
  *   and easgd_sync_round, with the same requirements; the workspace must hold
  *   easgd_mlp_round_workspace_bytes(...) bytes.
+ *   rho == 0 makes the call a local step: with rho = 0 Eq. (1) (Eq. (5),(6)) is a plain
+ *   (momentum) SGD step of every worker and Eq. (2) leaves the center as it is, so no
+ *   exchange is launched and Wc is not written.  A caller who wants workers to
+ *   exchange only every tau-th round (a communication period; an extension, the
+ *   paper's Sync EASGD exchanges in every round) passes rho = 0 in the rounds between.
  * Errors: as easgd_grad.
  */
 size_t easgd_mlp_round_workspace_bytes(const int *dims, int n_layers, int P, int b);

@@ -587,11 +587,15 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     if (head && (size_t)P * ((b + HEAD_ROWS - 1) / HEAD_ROWS) > 0x3fffffffull) return fail(EASGD_ERANGE, "%s: P*b too large", name);
 
     // ---- Eq. (2); beside forward propagation when the second stream is in use ----
+    // rho == 0: a local step.  Eq. (2) leaves the center as it is and Eq. (1) is a plain (momentum) SGD step, so
+    // the center rule is not launched at all and the worker rule reads the center in place (times zero).
+    const bool local_step = step && step->rho == 0.f;
     float *old_center = step ? reinterpret_cast<float *>(ws + pl.center_off) : nullptr;
+    const float *center_t = local_step ? step->Wc : old_center;
     std::unique_lock<std::mutex> lane_guard;
     SideLane *lane = nullptr;
     bool attach_center = false;
-    if (step) {
+    if (step && !local_step) {
         // Where Eq. (2) runs (EASGD_OPT_ROUND_OVERLAP): 0 = a kernel of its own on the caller's stream, 2 = the
         // same on the library's second stream, beside forward propagation, 3 = on extra blocks of the first
         // forward product's launch.  1 (default) chooses: the extra blocks when that launch leaves room on the
@@ -725,7 +729,7 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         if (step) {
             d.Wt = step->W + pl.off[l];
             d.Vt = step->V ? step->V + pl.off[l] : nullptr;
-            d.center = old_center + pl.off[l];
+            d.center = center_t + pl.off[l];
             d.eta = step->eta; d.rho = step->rho; d.alpha = step->eta * step->rho; d.delta = step->delta;
         }
         const bool vec = mult4(d_in) && mult4(d_out);

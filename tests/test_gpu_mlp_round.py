@@ -224,3 +224,43 @@ def test_shared_launches_change_nothing(hip, dims, P, b):
     for a, c in zip(out[0], out[1]):
         np.testing.assert_array_equal(a, c)
     np.testing.assert_array_equal(out[0][3], out[0][-1])      # the round's stored gradient is easgd_grad's
+
+
+@pytest.mark.parametrize("momentum", [False, True], ids=["easgd", "measgd"])
+def test_local_steps_between_exchanges(hip, momentum):
+    """rho = 0 makes the call a local step (no exchange): with a period of 3 the center changes only every third
+    round and stays bit for bit what it was in between (negative zeros included); every round matches the
+    oracle's rules applied to the stored gradients, with rho = 0 in the local rounds (Eq. (1) / (5),(6) at rho = 0
+    are the plain rules Eq. (3),(4) of one worker)."""
+    dims, P, b, tau = (40, 48, 10), 5, 20, 3
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=41)
+    Wc[::7] = F(-0.0)
+    wl = workloads.Workload("t", P=P, eta=ETA, rho=RHO, rounds=6, dims=tuple(dims), batch=b, N=N)
+    dW, dV, dWc = to_dev(W), to_dev(V), to_dev(Wc)
+    oW, oV, oWc = W.copy(), V.copy(), Wc.copy()
+    for t in range(6):
+        X, y = workloads.minibatch(wl, t, seed=41)
+        rho = RHO if (t + 1) % tau == 0 else 0.0
+        before = to_host(dWc).copy()
+        dG = torch.full_like(dW, float("nan"))
+        hip.easgd_mlp_round(dims, dW, dWc, to_dev(X), to_dev(y), ETA, rho, V=dV if momentum else None,
+                            delta=DELTA, G=dG)
+        G = to_host(dG)
+        if momentum:
+            oracle.measgd_round(oW, oV, G, oWc, F(ETA), F(rho), F(DELTA), N=N)
+        else:
+            oracle.easgd_round(oW, G, oWc, F(ETA), F(rho), N=N)
+        after = to_host(dWc)
+        if rho == 0.0:
+            assert after.tobytes() == before.tobytes(), f"round {t}: a local step wrote the center"
+            np.testing.assert_array_equal(oWc, before)          # and so says Eq. (2) at rho = 0
+        else:
+            assert not np.array_equal(after, before)
+        assert normwise(to_host(dW)[:, :N], oW[:, :N]) <= PER_ROUND_TOL, t
+        assert normwise(after, oWc) <= PER_ROUND_TOL, t
+        if momentum:
+            assert normwise(to_host(dV)[:, :N], oV[:, :N]) <= PER_ROUND_TOL, t
+        # teacher forcing: the next round starts from the device's state on both sides
+        oW[:, :N] = to_host(dW)[:, :N]; oWc[:] = after
+        if momentum:
+            oV[:, :N] = to_host(dV)[:, :N]

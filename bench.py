@@ -353,6 +353,8 @@ def main():
     ap.add_argument("--gemm-pair", type=int, default=None, choices=(0, 1),
                     help="library option EASGD_OPT_GEMM_PAIR: 0 = one launch per matrix product (tells the products "
                          "apart in a profile), default: the library's (shared launches)")
+    ap.add_argument("--gemm-xcd", type=int, default=None, choices=(0, 1, 2),
+                    help="library option EASGD_OPT_GEMM_XCD (block order of the matrix products), default: the library's")
     ap.add_argument("--mlp-head", type=int, default=None, choices=(0, 1),
                     help="library option EASGD_OPT_MLP_HEAD: 0 = the last layer as three launches, default: the "
                          "library's (one launch for a narrow last layer)")
@@ -371,6 +373,8 @@ def main():
         hip.set_option(hip.OPT_ROUND_OVERLAP, args.round_overlap)
     if args.gemm_pair is not None:
         hip.set_option(hip.OPT_GEMM_PAIR, args.gemm_pair)
+    if args.gemm_xcd is not None:
+        hip.set_option(hip.OPT_GEMM_XCD, args.gemm_xcd)
     if args.mlp_head is not None:
         hip.set_option(hip.OPT_MLP_HEAD, args.mlp_head)
     wl = workloads.WORKLOADS[args.workload]

@@ -48,6 +48,8 @@ struct GemmArgs {
     int tiles_m, tiles_n;
     int P;
     int xcd_chunk;                      // 0 = plain block order; else grid/8 (see the kernel)
+    int die_workers;                    // > 0 (needs xcd_chunk > 0, splits == 1, P == 8 * die_workers): a die walks its
+                                        // workers' tiles tile by tile, the workers of a tile next to each other
     // elastic epilogues: replica / momentum tiles indexed like C (worker stride c_ws, row stride ldc);
     // the center has the row stride ldc and no worker stride
     float *Wt, *Vt;
@@ -118,9 +120,19 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         id = (id & 7) * p.xcd_chunk + (id >> 3);
         if (id >= tiles * p.splits * p.P) return;
     }
-    const int tile = id % tiles; id /= tiles;
-    const int split = id % p.splits;
-    const int w = id / p.splits;
+    int tile, split, w;
+    if (p.die_workers > 0) {
+        // Elastic epilogues read the time-t center tile, which all workers share: with the tiles of a die's workers
+        // interleaved, the die fetches each center tile once instead of once per worker.
+        const int q = (int)(bid >> 3);
+        tile = q / p.die_workers;
+        split = 0;
+        w = (int)(bid & 7) * p.die_workers + q % p.die_workers;
+    } else {
+        tile = id % tiles; id /= tiles;
+        split = id % p.splits;
+        w = id / p.splits;
+    }
     const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
     const int k_begin = split * p.k_per_split;
     const int k_end = min(p.K, k_begin + p.k_per_split);

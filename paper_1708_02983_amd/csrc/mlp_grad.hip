@@ -382,9 +382,12 @@ static unsigned place_blocks(GemmArgs &a)
     a.tiles_n = (a.N + BN - 1) / BN;
     size_t total = (size_t)a.tiles_m * a.tiles_n * a.splits * a.P;
     a.xcd_chunk = 0;
+    a.die_workers = 0;
     if (options().gemm_xcd && total >= 64) {
         total = (total + 7) / 8 * 8;
         a.xcd_chunk = (int)(total / 8);
+        // a product with an elastic epilogue (it has a center): interleave the workers of a die
+        if (a.center && a.splits == 1 && a.P % 8 == 0 && options().gemm_xcd == 1) a.die_workers = a.P / 8;
     }
     return (unsigned)total;
 }

@@ -50,6 +50,9 @@ struct GemmArgs {
     int xcd_chunk;                      // 0 = plain block order; else grid/8 (see the kernel)
     int die_workers;                    // > 0 (needs xcd_chunk > 0, splits == 1, P == 8 * die_workers): a die walks its
                                         // workers' tiles tile by tile, the workers of a tile next to each other
+    // ceil(2^32 / d) for the three divisors of the block -> tile mapping (tiles per worker, tiles_n, die_workers),
+    // or 0 where the host could not guarantee that the product form is exact (then the kernel divides)
+    unsigned magic_tiles, magic_tiles_n, magic_die;
     // elastic epilogues: replica / momentum tiles indexed like C (worker stride c_ws, row stride ldc);
     // the center has the row stride ldc and no worker stride
     float *Wt, *Vt;
@@ -59,6 +62,17 @@ struct GemmArgs {
     // work in the shadow of matrix-core-bound work, without a second stream); ctr.blocks == 0: none
     CenterJob ctr;
 };
+
+// n / d for 0 <= n, d >= 1, with magic = ceil(2^32 / d) when n * d < 2^32 (then the high half of n * magic is the
+// quotient), magic = 0 otherwise.  A 32-bit division costs some thirty instructions of which most go through the
+// vector unit, where they queue behind the MFMAs of the other wavefronts of the SIMD; every block of a short product
+// pays for three of them before it can issue its first load.
+__device__ __forceinline__ int fast_div(int n, int d, unsigned magic)
+{
+    if (d == 1) return n;
+    if (magic == 0) return n / d;
+    return (int)__umulhi((unsigned)n, magic);
+}
 
 // Four elements idx0..idx0+3 along the contiguous axis of a row that starts at `row`.
 // Elements at or beyond `lim` read as 0, except index `ones` which reads as 1.
@@ -125,15 +139,22 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         // Elastic epilogues read the time-t center tile, which all workers share: with the tiles of a die's workers
         // interleaved, the die fetches each center tile once instead of once per worker.
         const int q = (int)(bid >> 3);
-        tile = q / p.die_workers;
+        tile = fast_div(q, p.die_workers, p.magic_die);
         split = 0;
-        w = (int)(bid & 7) * p.die_workers + q % p.die_workers;
+        w = (int)(bid & 7) * p.die_workers + (q - tile * p.die_workers);
     } else {
-        tile = id % tiles; id /= tiles;
-        split = id % p.splits;
-        w = id / p.splits;
+        const int rest = fast_div(id, tiles, p.magic_tiles);
+        tile = id - rest * tiles;
+        if (p.splits == 1) {
+            split = 0;
+            w = rest;
+        } else {
+            split = rest % p.splits;
+            w = rest / p.splits;
+        }
     }
-    const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+    const int tile_m = fast_div(tile, p.tiles_n, p.magic_tiles_n);
+    const int m0 = tile_m * BM, n0 = (tile - tile_m * p.tiles_n) * BN;
     const int k_begin = split * p.k_per_split;
     const int k_end = min(p.K, k_begin + p.k_per_split);
 

@@ -389,6 +389,15 @@ static unsigned place_blocks(GemmArgs &a)
         // a product with an elastic epilogue (it has a center): interleave the workers of a die
         if (a.center && a.splits == 1 && a.P % 8 == 0 && options().gemm_xcd == 1) a.die_workers = a.P / 8;
     }
+    // the kernel's divisions by multiplication: exact while dividend * divisor < 2^32
+    auto magic = [&](size_t dividend_max, int d) -> unsigned {
+        if (d <= 1 || dividend_max * (size_t)d >= ((size_t)1 << 32)) return 0u;
+        return (unsigned)((((size_t)1 << 32) + (size_t)d - 1) / (size_t)d);
+    };
+    const size_t tiles = (size_t)a.tiles_m * a.tiles_n;
+    a.magic_tiles = magic(total, (int)tiles);
+    a.magic_tiles_n = magic(tiles, a.tiles_n);
+    a.magic_die = magic(total / 8 + 1, a.die_workers);
     return (unsigned)total;
 }
 

@@ -405,9 +405,14 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         if (s < n_full) load_fast(k_begin + s * BK, ra, rb);
         else load_tail(k_begin + s * BK, ra, rb);
     };
+    // Tiles whose rows and columns all lie inside the operands have nothing to replace on the way to LDS; the
+    // replacement is one select per element and slab on the vector unit, which the MFMAs of the SIMD then wait for.
+    const bool inner_tile = ((A_LAYOUT == K_CONTIG) ? (m0 + BM <= p.M) : (m0 + BM <= p.a_lim)) &&
+                            ((B_LAYOUT == K_CONTIG) ? (n0 + BN <= p.N) : (n0 + BN <= b_lim));     // uniform
     auto store_slab = [&](int buf, int s, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
         if (s >= n_full) fix_tail(k_begin + s * BK, ra, rb);
-        store_lds(buf, ra, rb, true);
+        if (inner_tile) store_lds(buf, ra, rb, false);
+        else store_lds(buf, ra, rb, true);
     };
     auto k_in_slab = [&](int s) { return min(BK, k_end - (k_begin + s * BK)); };
 

@@ -21,6 +21,7 @@
 // MFMA operand fetch is one conflict-free ds_read_b32 per lane.
 #pragma once
 #include "common.h"
+#include <type_traits>
 #include "elastic_rule.h"
 
 namespace easgd {
@@ -409,10 +410,13 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     // replacement is one select per element and slab on the vector unit, which the MFMAs of the SIMD then wait for.
     const bool inner_tile = ((A_LAYOUT == K_CONTIG) ? (m0 + BM <= p.M) : (m0 + BM <= p.a_lim)) &&
                             ((B_LAYOUT == K_CONTIG) ? (n0 + BN <= p.N) : (n0 + BN <= b_lim));     // uniform
-    auto store_slab = [&](int buf, int s, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
-        if (s >= n_full) fix_tail(k_begin + s * BK, ra, rb);
+    auto store_full = [&](int buf, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {      // a slab fully inside along k
         if (inner_tile) store_lds(buf, ra, rb, false);
         else store_lds(buf, ra, rb, true);
+    };
+    auto store_slab = [&](int buf, int s, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {
+        if (s >= n_full) fix_tail(k_begin + s * BK, ra, rb);
+        store_full(buf, ra, rb);
     };
     auto k_in_slab = [&](int s) { return min(BK, k_end - (k_begin + s * BK)); };
 
@@ -428,6 +432,23 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         store_slab(0, 0, ra0, rb0);
         __syncthreads();
         int s = 0;
+        // The steady state proper: every slab it loads or stores lies fully inside the operands, so it contains
+        // nothing of the partial-slab handling (which the compiler otherwise folds into the loop as selects and
+        // per-lane address arithmetic on every slab; the vector unit is what the MFMAs wait for).
+        // (one copy of the loop per kind of tile, so that the kind is not a branch, and a register merge, per slab)
+        auto steady = [&](auto clamp) {
+            for (; s + 3 < n_full; s += 2) {
+                load_fast(k_begin + (s + 2) * BK, ra0, rb0);
+                multiply_slab(0, BK, [&] { store_lds(1, ra1, rb1, decltype(clamp)::value); });
+                __syncthreads();
+                load_fast(k_begin + (s + 3) * BK, ra1, rb1);
+                multiply_slab(1, BK, [&] { store_lds(0, ra0, rb0, decltype(clamp)::value); });
+                __syncthreads();
+            }
+        };
+        if (inner_tile) steady(std::false_type{});
+        else steady(std::true_type{});
+        // the same with the partial last slab allowed (at most one more trip)
         for (; s + 3 < n_pipe; s += 2) {
             load_slab(s + 2, ra0, rb0);
             multiply_slab(0, BK, [&] { store_slab(1, s + 1, ra1, rb1); });

@@ -406,10 +406,12 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         if (s < n_full) load_fast(k_begin + s * BK, ra, rb);
         else load_tail(k_begin + s * BK, ra, rb);
     };
-    // Tiles whose rows and columns all lie inside the operands have nothing to replace on the way to LDS; the
-    // replacement is one select per element and slab on the vector unit, which the MFMAs of the SIMD then wait for.
-    const bool inner_tile = ((A_LAYOUT == K_CONTIG) ? (m0 + BM <= p.M) : (m0 + BM <= p.a_lim)) &&
-                            ((B_LAYOUT == K_CONTIG) ? (n0 + BN <= p.N) : (n0 + BN <= b_lim));     // uniform
+    // Most tiles have nothing to replace on the way to LDS; the replacement is one select per element and slab on
+    // the vector unit, which the MFMAs of the SIMD then wait for.
+    // Rows of A beyond M and columns of B beyond N only reach elements of C that are never stored, so whatever the
+    // clamped loads brought for them may stay; the one thing that has to be replaced is the ones vector, which
+    // sits in the tile of an m/n-contiguous A that holds row a_ones.
+    const bool inner_tile = !(A_LAYOUT == MN_CONTIG && p.a_ones >= m0 && p.a_ones < m0 + BM);      // uniform
     auto store_full = [&](int buf, f32x4 (&ra)[IT_A], f32x4 (&rb)[IT_B]) {      // a slab fully inside along k
         if (inner_tile) store_lds(buf, ra, rb, false);
         else store_lds(buf, ra, rb, true);

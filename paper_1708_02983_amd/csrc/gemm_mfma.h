@@ -171,8 +171,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     const float *a_src[IT_A], *b_src[IT_B];   // source of the chunk in the slab that starts at k = 0
     int a_dst[IT_A], b_dst[IT_B];             // LDS offset of the chunk's first element
     bool a_ok[IT_A], b_ok[IT_B];              // false: the chunk lies outside the stored matrix (its address was
-                                              // clamped); zeros are stored instead, or 1 in lane a_one[it]
-    int a_one[IT_A];
+                                              // clamped); zeros are stored instead, or 1 where the ones vector sits
     int a_krel[IT_A], b_krel[IT_B];           // k of the chunk's first element relative to the slab start
 #pragma unroll
     for (int it = 0; it < IT_A; ++it) {
@@ -180,7 +179,6 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         if (A_LAYOUT == K_CONTIG) {
             const int kq = c % (BK / 4), m = c / (BK / 4);
             a_ok[it] = (m0 + m < p.M);
-            a_one[it] = -1;
             a_src[it] = A + (size_t)min(m0 + m, p.M - 1) * p.lda + 4 * kq;
             a_dst[it] = 4 * kq * PITCH_A + m;
             a_krel[it] = 4 * kq;
@@ -188,7 +186,6 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
             // with 128-bit loads a_lim is a multiple of 4, so a chunk is entirely inside or entirely outside
             const int mq = c % (BM / 4), k = c / (BM / 4), m = m0 + 4 * mq;
             a_ok[it] = (m + 3 < p.a_lim);
-            a_one[it] = (p.a_ones >= m && p.a_ones < m + 4) ? p.a_ones - m : -1;
             a_src[it] = A + (size_t)k * p.lda + (a_ok[it] ? m : 0);
             a_dst[it] = k * PITCH_A + 4 * mq;
             a_krel[it] = k;
@@ -304,8 +301,10 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                 for (int q = 0; q < 4; ++q) As[buf][a_dst[it] + q * PITCH_A] = v[q];
             } else {
                 if (clamped && !a_ok[it]) {
+                    // only the one tile that holds the ones vector comes here: its position is worked out on the spot
+                    const int m_chunk = m0 + 4 * ((tid + it * NTHREADS) % (BM / 4));
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) v[q] = (q == a_one[it]) ? 1.f : 0.f;
+                    for (int q = 0; q < 4; ++q) v[q] = (m_chunk + q == p.a_ones) ? 1.f : 0.f;
                 }
                 *reinterpret_cast<f32x4 *>(&As[buf][a_dst[it]]) = v;
             }

@@ -158,7 +158,8 @@ __global__ __launch_bounds__(64) void mean_loss_kernel(const float *__restrict__
 // registers, and uses them for both products:
 //   z[r][c]  = sum_n A[r][n] W_L[n][c] + b_L[c]   per thread ascending n, then a fixed exchange tree over the
 //                                                  lanes, then the four wavefronts in ascending order, then b_L
-//   dz[r][c] = (softmax(z[r])[c] - [c == y_r]) / b,   row_loss[r] = -log softmax(z[r])[y_r]
+//   dz[r][c] = (softmax(z[r])[c] - [c == y_r]) / b,   row_loss[r] = -log softmax(z[r])[y_r]   16 lanes per row, one
+//                                                  class each; maximum and sum by fixed xor trees
 //   da[r][n] = sum_c dz[r][c] W_L[n][c] (ascending c), zero where A[r][n] <= 0
 // Blocks are numbered worker-fastest, so that with P a multiple of 8 all blocks of a worker run on one die and
 // share its copy of W_L in that die's L2.
@@ -281,43 +282,33 @@ __global__ __launch_bounds__(256) void mlp_head_kernel(HeadArgs h)
     }
     __syncthreads();
 
-    // softmax cross-entropy: one thread per sample row
-    if (tid < ROWS) {
-        const int rr = tid;
-        float d[CP];
-#pragma unroll
-        for (int c = 0; c < CP; ++c) d[c] = 0.f;
-        if (rr < rows_here) {
-            const size_t grow = (size_t)w * h.b + r0 + rr;
-            const int label = h.y[grow];
-            float z[CP];
-            float zmax = -INFINITY;
-#pragma unroll
-            for (int c = 0; c < CP; ++c)
-                if (c < C) {
-                    const int i = rr * CP + c;
-                    z[c] = (((part[0][i] + part[1][i]) + part[2][i]) + part[3][i]) + Wg[(size_t)K * C + c];
-                    zmax = fmaxf(zmax, z[c]);
-                }
-            float sum = 0.f, zlabel = 0.f;
-#pragma unroll
-            for (int c = 0; c < CP; ++c)
-                if (c < C) {
-                    if (c == label) zlabel = z[c] - zmax;
-                    z[c] = expf(z[c] - zmax);
-                    sum += z[c];
-                }
-            const float inv_sum = 1.0f / sum, inv_b = 1.0f / (float)h.b;
-#pragma unroll
-            for (int c = 0; c < CP; ++c)
-                if (c < C) {
-                    d[c] = (z[c] * inv_sum - (c == label ? 1.f : 0.f)) * inv_b;
-                    h.dz[grow * (size_t)C + c] = d[c];
-                }
-            h.row_loss[grow] = logf(sum) - zlabel;
+    // softmax cross-entropy: 16 lanes per sample row, one class each; maximum and sum over the row's lanes by
+    // fixed xor trees
+    static_assert(ROWS * 16 <= 64 && CP <= 16, "the rows of a block share one wavefront");
+    if (tid < ROWS * 16) {
+        const int rr = tid >> 4, c = tid & 15;
+        const bool row_ok = rr < rows_here, live = row_ok && c < C;
+        const size_t grow = (size_t)w * h.b + r0 + (row_ok ? rr : 0);
+        const int label = h.y[grow];
+        float z = -INFINITY;
+        if (live) {
+            const int i = rr * CP + c;
+            z = (((part[0][i] + part[1][i]) + part[2][i]) + part[3][i]) + Wg[(size_t)K * C + c];
         }
+        float zmax = z;
 #pragma unroll
-        for (int c = 0; c < CP; ++c) dzs[rr][c] = d[c];
+        for (int o = 8; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o));
+        const float e = live ? expf(z - zmax) : 0.f;
+        float sum = e;
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        float zlabel = (live && c == label) ? z - zmax : 0.f;     // one lane of the row holds it
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) zlabel += __shfl_xor(zlabel, o);
+        const float d = live ? (e / sum - (c == label ? 1.f : 0.f)) / (float)h.b : 0.f;
+        if (live) h.dz[grow * (size_t)C + c] = d;
+        if (c < CP) dzs[rr][c] = d;
+        if (row_ok && c == 0) h.row_loss[grow] = logf(sum) - zlabel;
     }
     if (!h.da) return;                                                         // uniform
     __syncthreads();

@@ -264,3 +264,34 @@ def test_local_steps_between_exchanges(hip, momentum):
         oW[:, :N] = to_host(dW)[:, :N]; oWc[:] = after
         if momentum:
             oV[:, :N] = to_host(dV)[:, :N]
+
+
+@pytest.mark.parametrize("dims,P,b", [((200, 264, 136, 10), 8, 100), ((512, 384, 10), 40, 128), ((300, 260, 10), 16, 64)],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_block_order_changes_nothing(hip, dims, P, b):
+    """EASGD_OPT_GEMM_XCD only renumbers the blocks of a product (plain order; whole workers per die; a die's workers
+    interleaved tile by tile in the products that apply the worker rule): every block computes the same tile the
+    same way, so rounds and gradients are the same bits under all three orders (P a multiple of 8 makes the third
+    order differ from the second)."""
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=37)
+    dX, dy = to_dev(X), to_dev(y)
+    old = hip.get_option(hip.OPT_GEMM_XCD)
+    out = []
+    try:
+        for order in (0, 1, 2):
+            hip.set_option(hip.OPT_GEMM_XCD, order)
+            res = []
+            for momentum in (False, True):
+                fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
+                fG = torch.full_like(fW, float("nan"))
+                hip.easgd_mlp_round(dims, fW, fWc, dX, dy, ETA, RHO, V=fV if momentum else None, delta=DELTA, G=fG)
+                res += [to_host(fW), to_host(fV), to_host(fWc), to_host(fG)]
+            gW = to_dev(W); gG = torch.full_like(gW, float("nan"))
+            hip.easgd_grad(dims, gW, dX, dy, gG)
+            res.append(to_host(gG))
+            out.append(res)
+    finally:
+        hip.set_option(hip.OPT_GEMM_XCD, old)
+    for other in out[1:]:
+        for a, c in zip(out[0], other):
+            np.testing.assert_array_equal(a, c)

@@ -19,7 +19,8 @@
  *   - the return value is an easgd_status; on error nothing was launched and
  *     easgd_last_error() describes the reason (thread-local string);
  *   - buffers of one call must not overlap each other;
- *   - all floating point is IEEE fp32 (storage and arithmetic);
+ *   - all floating point is IEEE fp32 (storage and arithmetic), except the two *_bf16 entry points,
+ *     which keep fp32 arithmetic and store gradients and momentum buffers as bfloat16;
  *   - replica matrices are [P][ld] row-major: row i is worker i, its first N
  *     entries are the parameters, entries [N, ld) are padding that is never
  *     read or written.
@@ -86,6 +87,37 @@ int easgd_sync_round(float *W, const float *G, float *Wc,
 int measgd_round(float *W, float *V, const float *G, float *Wc,
                  int P, size_t N, size_t ld,
                  float eta, float rho, float delta, void *stream);
+
+/*
+ * The two rounds above with the gradients (and the momentum buffers) STORED as bfloat16 -- an
+ * extension: the paper keeps fp32 throughout and names low precision only as future work (Section 3.2).
+ * Replicas and center stay fp32, all arithmetic is fp32; the HBM stream shrinks from N*(12P+8) to
+ * N*(10P+8) bytes per round (Eq. (1)) and from N*(20P+8) to N*(14P+8) bytes (Eq. (5),(6)).
+ *
+ * A bfloat16 is the upper 16 bits of an IEEE fp32, passed as uint16_t.  Widening is exact.  Narrowing
+ * rounds to nearest, ties to even; values beyond the largest finite bfloat16 become infinity; a NaN
+ * becomes 0x7FC0 with the input's sign.  With g = widened G[i][j], v = widened V[i][j]:
+ *
+ *     V[i][j] <- narrow( fl(fl(delta*v) - fl(eta*g)) )       Eq. (5): three fp32 operations, each
+ *                                                            rounded on its own (no fused multiply-add),
+ *                                                            so the stored code is reproducible anywhere
+ *     W[i][j] <- W[i][j] + widened V[i][j](new) - eta*rho*d_i                    Eq. (6)
+ *     easgd_sync_round_bf16:  W[i][j] <- W[i][j] - eta*(g + rho*d_i)             Eq. (1)
+ *     Wc as in easgd_sync_round                                                  Eq. (2)
+ *
+ *   W   DEVICE in/out [P][ld] fp32;  Wc  DEVICE in/out [N] fp32
+ *   G   DEVICE in     [P][ld] bfloat16 (never written);  V  DEVICE in/out [P][ld] bfloat16
+ *   ld counts elements and is the same for W, G and V.
+ * Fast path: W, Wc 16-byte aligned, G, V 8-byte aligned, ld % 4 == 0; otherwise a scalar kernel
+ * computes the same values.  The sum of Eq. (2) is taken in ascending worker order by one thread.
+ * Errors: EASGD_EINVAL, EASGD_ELAUNCH.
+ */
+int easgd_sync_round_bf16(float *W, const uint16_t *G, float *Wc,
+                          int P, size_t N, size_t ld,
+                          float eta, float rho, void *stream);
+int measgd_round_bf16(float *W, uint16_t *V, const uint16_t *G, float *Wc,
+                      int P, size_t N, size_t ld,
+                      float eta, float rho, float delta, void *stream);
 
 /*
  * Synchronous data-parallel SGD on the same replicas, the method's point of comparison (Section 2.3,

@@ -1,0 +1,229 @@
+// The fused elastic exchange-and-update (Section 5.1 steps (2)-(5); Eq. (1), (2), (5), (6)) with the
+// gradients and the momentum buffers STORED as bfloat16 -- an extension: the paper keeps everything in
+// fp32 and only names low precision as future work (Section 3.2).  Replicas and center stay fp32 and
+// all arithmetic is fp32; what changes is the HBM stream: N*(10P+8) bytes per round instead of
+// N*(12P+8) (EASGD), N*(14P+8) instead of N*(20P+8) (momentum).
+//
+// bfloat16 = the upper 16 bits of an fp32.  Widening is exact.  Narrowing rounds to nearest, ties to
+// even; beyond the largest finite value it gives infinity; a NaN becomes 0x7FC0 with the input's sign.
+// Eq. (5) decides a stored code, so its arithmetic is pinned: fl(fl(delta*v) - fl(eta*g)), no fused
+// multiply-add, then narrowed; Eq. (6) adds the stored (narrowed) V_{t+1}.
+//
+// Same skeleton as elastic_vec4_kernel: a block owns GROUPS*256 groups of four consecutive parameters
+// and walks the workers in ascending order (fixed summation order for Eq. (2)).
+#include "common.h"
+
+namespace easgd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_widen(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
+
+__device__ __forceinline__ unsigned short bf16_narrow(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)(((u >> 16) & 0x8000u) | 0x7fc0u);
+    // adds just under half a unit of the kept part, and one more if the kept part is odd: ties go to even
+    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// One worker's rule on one parameter.  Returns d = w - c (time-t values).
+template <bool MOM>
+__device__ __forceinline__ float worker_rule_bf16(float &w, unsigned short &v16, unsigned short g16, float c,
+                                                  float eta, float rho, float alpha, float delta)
+{
+    const float d = w - c;
+    const float g = bf16_widen(g16);
+    if constexpr (MOM) {
+        float cand;
+        {
+#pragma clang fp contract(off)
+            const float dv = delta * bf16_widen(v16);
+            const float eg = eta * g;
+            cand = dv - eg;                   // Eq. (5), each operation rounded on its own
+        }
+        v16 = bf16_narrow(cand);
+        w = (w + bf16_widen(v16)) - alpha * d;   // Eq. (6) with V_{t+1} as stored
+    } else {
+        w = w - eta * (g + rho * d);          // Eq. (1)
+    }
+    return d;
+}
+
+template <bool MOM>
+__device__ __forceinline__ void scalar_param(float *__restrict__ W, unsigned short *__restrict__ V,
+                                             const unsigned short *__restrict__ G, float *__restrict__ Wc,
+                                             int P, size_t j, size_t ld, float eta, float rho, float alpha, float delta)
+{
+    const float c = Wc[j];
+    float acc = 0.f;
+    for (int i = 0; i < P; ++i) {             // ascending worker order
+        const size_t k = (size_t)i * ld + j;
+        float w = W[k];
+        unsigned short v = 0;
+        if constexpr (MOM) v = V[k];
+        acc += worker_rule_bf16<MOM>(w, v, G[k], c, eta, rho, alpha, delta);
+        W[k] = w;
+        if constexpr (MOM) V[k] = v;
+    }
+    Wc[j] = c + alpha * acc;                  // Eq. (2)
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ T lp_load(const T *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void lp_store(T *p, T v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// 128-bit accesses to W and Wc, 64-bit accesses to the bfloat16 rows.  The N % 4 tail rides on the last block.
+template <bool MOM, bool NT, int GROUPS>
+__global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restrict__ Wp, unsigned short *__restrict__ Vp,
+                                                                const unsigned short *__restrict__ Gp,
+                                                                float *__restrict__ Wcp, int P, size_t N, size_t ld,
+                                                                float eta, float rho, float alpha, float delta)
+{
+    f32x4 *__restrict__ W = (f32x4 *)Wp;
+    u16x4 *__restrict__ V = (u16x4 *)Vp;
+    const u16x4 *__restrict__ G = (const u16x4 *)Gp;
+    f32x4 *__restrict__ Wc = (f32x4 *)Wcp;
+    const size_t n4 = N / 4, ld4 = ld / 4;
+    constexpr size_t TILE = (size_t)GROUPS * 256;
+    const size_t n_tiles = (n4 + TILE - 1) / TILE;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const size_t j0 = t * TILE + threadIdx.x;
+        f32x4 c[GROUPS], acc[GROUPS];
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * 256;
+            c[q] = (j < n4) ? Wc[j] : zero;
+            acc[q] = zero;
+        }
+        for (int i = 0; i < P; ++i) {
+            const size_t row = (size_t)i * ld4;
+            f32x4 w[GROUPS];
+            u16x4 g[GROUPS], v[GROUPS];
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * 256;
+                if (j < n4) {
+                    w[q] = lp_load<NT>(W + row + j);
+                    g[q] = lp_load<NT>(G + row + j);
+                    if constexpr (MOM) v[q] = lp_load<NT>(V + row + j);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * 256;
+                if (j < n4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float we = w[q][e];
+                        unsigned short ve = 0;
+                        if constexpr (MOM) ve = v[q][e];
+                        acc[q][e] += worker_rule_bf16<MOM>(we, ve, g[q][e], c[q][e], eta, rho, alpha, delta);
+                        w[q][e] = we;
+                        if constexpr (MOM) v[q][e] = ve;
+                    }
+                    lp_store<NT>(W + row + j, w[q]);
+                    if constexpr (MOM) lp_store<NT>(V + row + j, v[q]);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * 256;
+            if (j < n4) Wc[j] = c[q] + alpha * acc[q];   // Eq. (2)
+        }
+    }
+    const size_t tail = N - n4 * 4;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail)
+        scalar_param<MOM>(Wp, Vp, Gp, Wcp, P, n4 * 4 + threadIdx.x, ld, eta, rho, alpha, delta);
+}
+
+// Any alignment: one thread per parameter.
+template <bool MOM>
+__global__ __launch_bounds__(256) void elastic_bf16_scalar_kernel(float *__restrict__ W, unsigned short *__restrict__ V,
+                                                                  const unsigned short *__restrict__ G,
+                                                                  float *__restrict__ Wc, int P, size_t N, size_t ld,
+                                                                  float eta, float rho, float alpha, float delta)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += stride)
+        scalar_param<MOM>(W, V, G, Wc, P, j, ld, eta, rho, alpha, delta);
+}
+
+template <bool MOM, bool NT>
+static void launch_bf16(int groups, dim3 grid, hipStream_t s, float *W, unsigned short *V, const unsigned short *G,
+                        float *Wc, int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
+{
+    switch (groups) {
+    case 1: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 2: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    default: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    }
+}
+
+inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
+
+template <bool MOM>
+static int elastic_round_bf16(float *W, unsigned short *V, const unsigned short *G, float *Wc, int P, size_t N, size_t ld,
+                              float eta, float rho, float delta, void *stream)
+{
+    const char *name = MOM ? "measgd_round_bf16" : "easgd_sync_round_bf16";
+    if (!W || !G || !Wc || (MOM && !V)) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
+    if (P < 1) return fail(EASGD_EINVAL, "%s: P must be >= 1, got %d", name, P);
+    if (N == 0) return fail(EASGD_EINVAL, "%s: N must be >= 1", name);
+    if (ld < N) return fail(EASGD_EINVAL, "%s: ld (%zu) < N (%zu)", name, ld, N);
+    clear_error();
+
+    const Options &opt = options();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const float alpha = eta * rho;
+    const bool vec = aligned16(W) && aligned16(Wc) && aligned8(G) && (!MOM || aligned8(V)) && (ld % 4 == 0);
+    // fewer groups per thread for small N, so that the grid still covers the chip several times
+    size_t groups = (size_t)opt.update_groups;
+    while (groups > 1 && N / 4 / (groups * 256) < (size_t)(4 * num_cus())) groups /= 2;
+    size_t blocks = vec ? (N / 4 + groups * 256 - 1) / (groups * 256) : (N + 255) / 256;
+    if (blocks == 0) blocks = 1;
+    if (opt.update_blocks_per_cu > 0) {
+        const size_t persistent = (size_t)opt.update_blocks_per_cu * (size_t)num_cus();
+        if (blocks > persistent) blocks = persistent;
+    }
+    if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
+    const dim3 grid((unsigned)blocks);
+    if (!vec)
+        hipLaunchKernelGGL((elastic_bf16_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    else if (opt.update_nontemporal)
+        launch_bf16<MOM, true>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    else
+        launch_bf16<MOM, false>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    return check_launch(name);
+}
+
+}  // namespace easgd
+
+extern "C" {
+
+int easgd_sync_round_bf16(float *W, const uint16_t *G, float *Wc, int P, size_t N, size_t ld,
+                          float eta, float rho, void *stream)
+{
+    return easgd::elastic_round_bf16<false>(W, nullptr, G, Wc, P, N, ld, eta, rho, 0.0f, stream);
+}
+
+int measgd_round_bf16(float *W, uint16_t *V, const uint16_t *G, float *Wc, int P, size_t N, size_t ld,
+                      float eta, float rho, float delta, void *stream)
+{
+    return easgd::elastic_round_bf16<true>(W, V, G, Wc, P, N, ld, eta, rho, delta, stream);
+}
+
+}  // extern "C"

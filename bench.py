@@ -205,7 +205,8 @@ def bench_host_fed(hip, wl, steps, warmup):
 
 def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
     """rule = "elastic": the workload's EASGD / MEASGD update; "sync_sgd": the synchronous data-parallel SGD
-    round on the same replicas and gradients (every replica moves by the gradient sum)."""
+    round on the same replicas and gradients (every replica moves by the gradient sum); "elastic_bf16": the
+    workload's update with gradients and momentum buffers stored as bfloat16 (an extension)."""
     import torch
     P, N = wl.P, wl.N
     dW = workloads.device_normal((P, N), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 1)
@@ -213,9 +214,16 @@ def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
     dV = torch.zeros_like(dW) if wl.momentum else None
     # gradients of consecutive rounds: a small pool of independent draws, cycled (footprint >> caches)
     Gs = [workloads.device_normal((P, N), workloads.GRADIENT_STD, workloads.DEFAULT_SEED, 100 + t) for t in range(pool)]
+    if rule == "elastic_bf16":
+        Gs = [g.to(torch.bfloat16) for g in Gs]
+        dV = torch.zeros((P, N), dtype=torch.bfloat16, device="cuda") if wl.momentum else None
 
     def step(t):
-        if rule == "sync_sgd":
+        if rule == "elastic_bf16" and wl.momentum:
+            hip.measgd_round_bf16(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta)
+        elif rule == "elastic_bf16":
+            hip.easgd_sync_round_bf16(dW, Gs[t % pool], dWc, wl.eta, wl.rho)
+        elif rule == "sync_sgd":
             hip.sync_sgd_round(dW, Gs[t % pool], wl.eta / P, V=dV, delta=wl.delta or 0.0)
         elif wl.momentum:
             hip.measgd_round(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta)
@@ -442,6 +450,22 @@ def main():
                          "algorithmic_bytes_per_launch": sgd_bytes, "avg_launch_ms": round(r3["update_ms"], 4),
                          "frac_of_triad_ceiling": round(gbs / ceiling, 4)}}
         torch.cuda.empty_cache()
+        # an extension (the paper names low precision only as future work): the same updates with gradients and
+        # momentum buffers stored as bfloat16, fp32 replicas, center and arithmetic
+        for name in ("cfg4", "cfg5"):
+            w5 = workloads.WORKLOADS[name]
+            r5 = bench_update_only(hip, w5, 100, 5, rule="elastic_bf16")
+            lp_bytes = w5.N * ((14 if w5.momentum else 10) * w5.P + 8)
+            gbs = lp_bytes / (r5["update_ms"] * 1e-3) / 1e9
+            extra[name + "_bf16_storage"] = {
+                "workload": DESCRIPTIONS[name] + "; gradients" + (" and momentum buffers" if w5.momentum else "")
+                            + " stored as bfloat16 (extension)",
+                "rounds_per_s": round(100 / r5["elapsed_s"], 2), "ms_per_step": round(r5["ms_per_step"], 4),
+                "roofline": {"bound": "hbm", "kernel": "elastic_bf16_vec4_kernel", "achieved": round(gbs, 1),
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                             "algorithmic_bytes_per_launch": lp_bytes, "avg_launch_ms": round(r5["update_ms"], 4),
+                             "frac_of_triad_ceiling": round(gbs / ceiling, 4)}}
+            torch.cuda.empty_cache()
         line["elastic_update"] = extra
 
     if not args.no_cpu_baseline:

@@ -270,6 +270,11 @@ MEASURED_TRAFFIC_BYTES = {
     (False, 8, 61_000_000): 2_025_422.5 * 1024 * 2.000 + 2_144_537.9 * 1024 * 1.000,
     (True, 16, 61_000_000): 5_838_007.1 * 1024 * 2.000 + 7_863_305.8 * 1024 * 1.000,
 }
+# the same for the kernels with bfloat16-stored gradients (and momentum buffers)
+MEASURED_TRAFFIC_BYTES_BF16 = {
+    (False, 8, 61_000_000): 1_548_854.4 * 1024 * 2.000 + 2_144_545.8 * 1024 * 1.000,
+    (True, 16, 61_000_000): 3_931_683.7 * 1024 * 2.000 + 5_957_037.5 * 1024 * 1.000,
+}
 
 
 # HBM bytes per easgd_grad launch (all its kernels), measured the same way; see profiles/easgd_grad_cfg2_hbm_traffic.md.
@@ -462,7 +467,8 @@ def main():
                             + " stored as bfloat16 (extension)",
                 "rounds_per_s": round(100 / r5["elapsed_s"], 2), "ms_per_step": round(r5["ms_per_step"], 4),
                 "roofline": {"bound": "hbm", "kernel": "elastic_bf16_vec4_kernel", "achieved": round(gbs, 1),
-                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                             "traffic": MEASURED_TRAFFIC_BYTES_BF16.get((w5.momentum, w5.P, w5.N)),
                              "algorithmic_bytes_per_launch": lp_bytes, "avg_launch_ms": round(r5["update_ms"], 4),
                              "frac_of_triad_ceiling": round(gbs / ceiling, 4)}}
             torch.cuda.empty_cache()

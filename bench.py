@@ -11,8 +11,10 @@ rounds are also timed through the two-call path, `easgd_grad` followed by
 matrix-product kernels for the MFMA roofline.  For the update-only workloads
 cfg4/cfg5 a step is the elastic update alone.
 The default workload is cfg2 (MLP 784-1024-1024-10, P=16, b=128); the default
-run also measures the elastic update at AlexNet size (cfg4, cfg5) and reports
-those under "elastic_update" in the same JSON line.
+run also measures the elastic update at AlexNet size (cfg4, cfg5; with fp32 and
+with bfloat16-stored gradients and momentum buffers, the latter an extension)
+and the synchronous SGD round, and reports those under "elastic_update" in the
+same JSON line.
 
 Prints ONE JSON line.  Kernel-phase durations are measured with HIP events on
 the stream the kernels are launched on.

@@ -19,7 +19,7 @@
  *   - the return value is an easgd_status; on error nothing was launched and
  *     easgd_last_error() describes the reason (thread-local string);
  *   - buffers of one call must not overlap each other;
- *   - all floating point is IEEE fp32 (storage and arithmetic), except the two *_bf16 entry points,
+ *   - all floating point is IEEE fp32 (storage and arithmetic), except the *_bf16 / *_bf16v entry points,
  *     which keep fp32 arithmetic and store gradients and momentum buffers as bfloat16;
  *   - replica matrices are [P][ld] row-major: row i is worker i, its first N
  *     entries are the parameters, entries [N, ld) are padding that is never
@@ -118,6 +118,14 @@ int easgd_sync_round_bf16(float *W, const uint16_t *G, float *Wc,
 int measgd_round_bf16(float *W, uint16_t *V, const uint16_t *G, float *Wc,
                       int P, size_t N, size_t ld,
                       float eta, float rho, float delta, void *stream);
+/*
+ * measgd_round_bf16 for gradients that arrive as fp32 (what easgd_grad writes): only the momentum buffers
+ * are stored as bfloat16; g in Eq. (5) above is G[i][j] itself.  N*(16P+8) bytes per round.
+ * G DEVICE in [P][ld] fp32, 16-byte aligned for the fast path; everything else as for measgd_round_bf16.
+ */
+int measgd_round_bf16v(float *W, uint16_t *V, const float *G, float *Wc,
+                       int P, size_t N, size_t ld,
+                       float eta, float rho, float delta, void *stream);
 
 /*
  * Synchronous data-parallel SGD on the same replicas, the method's point of comparison (Section 2.3,

@@ -54,7 +54,8 @@ def easgd_round_bf16(W: np.ndarray, G16: np.ndarray, Wc: np.ndarray, eta: float,
 
 def measgd_round_bf16(W: np.ndarray, V16: np.ndarray, G16: np.ndarray, Wc: np.ndarray,
                       eta: float, rho: float, mu: float) -> None:
-    """Eq. (5)+(6)+(2) in place on W[P][ld] (fp32), V16[P][ld] (bfloat16 patterns) and Wc[N] (fp32)."""
+    """Eq. (5)+(6)+(2) in place on W[P][ld] (fp32), V16[P][ld] (bfloat16 patterns) and Wc[N] (fp32).
+    G16[P][ld]: the gradients, as bfloat16 patterns (uint16) or, when only V is stored in 16 bits, as fp32."""
     if not (W.dtype == np.float32 and Wc.dtype == np.float32 and W.ndim == 2 and Wc.ndim == 1):
         raise TypeError("W[P][ld] and Wc[N] must be float32")
     P, ld = W.shape
@@ -62,12 +63,17 @@ def measgd_round_bf16(W: np.ndarray, V16: np.ndarray, G16: np.ndarray, Wc: np.nd
     if ld < N:
         raise ValueError("ld < N")
     _check16("V16", V16, W.shape)
-    _check16("G16", G16, W.shape)
+    if G16.dtype == np.float32:
+        if G16.shape != W.shape:
+            raise ValueError("G has the wrong shape")
+        g = np.ascontiguousarray(G16[:, :N])
+    else:
+        _check16("G16", G16, W.shape)
+        g = bf16_widen(G16[:, :N])
     c = Wc.astype(np.float64)                                   # Wc_t, seen by every worker
     w = W[:, :N].astype(np.float64)
     d = w - c[None, :]                                          # W^i_t - Wc_t
     v = bf16_widen(V16[:, :N])
-    g = bf16_widen(G16[:, :N])
     # Eq. (5) in fp32, one rounding per operation, then narrowed: this is the value that is stored
     cand = np.float32(mu) * v - np.float32(eta) * g
     v16_new = bf16_round(cand)

@@ -49,6 +49,8 @@ def _load() -> ctypes.CDLL:
     lib.easgd_sync_round_bf16.restype = i
     lib.measgd_round_bf16.argtypes = [vp, vp, vp, vp, i, sz, sz, f, f, f, vp]
     lib.measgd_round_bf16.restype = i
+    lib.measgd_round_bf16v.argtypes = [vp, vp, vp, vp, i, sz, sz, f, f, f, vp]
+    lib.measgd_round_bf16v.restype = i
     lib.sync_sgd_round.argtypes = [vp, vp, vp, i, sz, sz, f, f, vp]
     lib.sync_sgd_round.restype = i
     ip = ctypes.POINTER(ctypes.c_int)
@@ -147,6 +149,16 @@ def measgd_round_bf16(W, V16, G16, Wc, eta: float, rho: float, delta: float, N: 
     _check(_lib.measgd_round_bf16(_dev("W", W, torch.float32, need), _dev("V16", V16, torch.bfloat16, need),
                                   _dev("G16", G16, torch.bfloat16, need), _dev("Wc", Wc, torch.float32, N),
                                   P, N, ld, eta, rho, delta, _stream(stream)))
+
+
+def measgd_round_bf16v(W, V16, G, Wc, eta: float, rho: float, delta: float, N: Optional[int] = None,
+                       stream=None) -> None:
+    """measgd_round with only the momentum buffers stored as bfloat16; the gradients are fp32; an extension."""
+    P, ld, N = _replica_shape(W, N)
+    need = (P - 1) * ld + N
+    _check(_lib.measgd_round_bf16v(_dev("W", W, torch.float32, need), _dev("V16", V16, torch.bfloat16, need),
+                                   _dev("G", G, torch.float32, need), _dev("Wc", Wc, torch.float32, N),
+                                   P, N, ld, eta, rho, delta, _stream(stream)))
 
 
 def sync_sgd_round(W, G, eta: float, V=None, delta: float = 0.0, N: Optional[int] = None, stream=None) -> None:

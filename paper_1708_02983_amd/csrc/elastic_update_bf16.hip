@@ -2,7 +2,8 @@
 // gradients and the momentum buffers STORED as bfloat16 -- an extension: the paper keeps everything in
 // fp32 and only names low precision as future work (Section 3.2).  Replicas and center stay fp32 and
 // all arithmetic is fp32; what changes is the HBM stream: N*(10P+8) bytes per round instead of
-// N*(12P+8) (EASGD), N*(14P+8) instead of N*(20P+8) (momentum).
+// N*(12P+8) (EASGD), N*(14P+8) instead of N*(20P+8) (momentum), N*(16P+8) when only the momentum
+// buffers are stored in 16 bits and the gradients arrive as fp32 (as easgd_grad writes them).
 //
 // bfloat16 = the upper 16 bits of an fp32.  Widening is exact.  Narrowing rounds to nearest, ties to
 // even; beyond the largest finite value it gives infinity; a NaN becomes 0x7FC0 with the input's sign.
@@ -30,11 +31,10 @@ __device__ __forceinline__ unsigned short bf16_narrow(float x)
 
 // One worker's rule on one parameter.  Returns d = w - c (time-t values).
 template <bool MOM>
-__device__ __forceinline__ float worker_rule_bf16(float &w, unsigned short &v16, unsigned short g16, float c,
+__device__ __forceinline__ float worker_rule_bf16(float &w, unsigned short &v16, float g, float c,
                                                   float eta, float rho, float alpha, float delta)
 {
     const float d = w - c;
-    const float g = bf16_widen(g16);
     if constexpr (MOM) {
         float cand;
         {
@@ -51,9 +51,13 @@ __device__ __forceinline__ float worker_rule_bf16(float &w, unsigned short &v16,
     return d;
 }
 
-template <bool MOM>
+// A gradient element as fp32: GT = unsigned short (bfloat16 storage) or float.
+__device__ __forceinline__ float grad_value(unsigned short g) { return bf16_widen(g); }
+__device__ __forceinline__ float grad_value(float g) { return g; }
+
+template <bool MOM, typename GT>
 __device__ __forceinline__ void scalar_param(float *__restrict__ W, unsigned short *__restrict__ V,
-                                             const unsigned short *__restrict__ G, float *__restrict__ Wc,
+                                             const GT *__restrict__ G, float *__restrict__ Wc,
                                              int P, size_t j, size_t ld, float eta, float rho, float alpha, float delta)
 {
     const float c = Wc[j];
@@ -63,7 +67,7 @@ __device__ __forceinline__ void scalar_param(float *__restrict__ W, unsigned sho
         float w = W[k];
         unsigned short v = 0;
         if constexpr (MOM) v = V[k];
-        acc += worker_rule_bf16<MOM>(w, v, G[k], c, eta, rho, alpha, delta);
+        acc += worker_rule_bf16<MOM>(w, v, grad_value(G[k]), c, eta, rho, alpha, delta);
         W[k] = w;
         if constexpr (MOM) V[k] = v;
     }
@@ -84,16 +88,22 @@ __device__ __forceinline__ void lp_store(T *p, T v)
     else *p = v;
 }
 
-// 128-bit accesses to W and Wc, 64-bit accesses to the bfloat16 rows.  The N % 4 tail rides on the last block.
-template <bool MOM, bool NT, int GROUPS>
+template <typename T> struct Vec4;
+template <> struct Vec4<float> { typedef f32x4 type; };
+template <> struct Vec4<unsigned short> { typedef u16x4 type; };
+
+// 128-bit accesses to the fp32 rows, 64-bit accesses to the bfloat16 rows.  The N % 4 tail rides on the last block.
+// GT: storage type of the gradients (unsigned short = bfloat16, or float when only V is stored in 16 bits).
+template <bool MOM, bool NT, int GROUPS, typename GT>
 __global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restrict__ Wp, unsigned short *__restrict__ Vp,
-                                                                const unsigned short *__restrict__ Gp,
+                                                                const GT *__restrict__ Gp,
                                                                 float *__restrict__ Wcp, int P, size_t N, size_t ld,
                                                                 float eta, float rho, float alpha, float delta)
 {
+    typedef typename Vec4<GT>::type g4;
     f32x4 *__restrict__ W = (f32x4 *)Wp;
     u16x4 *__restrict__ V = (u16x4 *)Vp;
-    const u16x4 *__restrict__ G = (const u16x4 *)Gp;
+    const g4 *__restrict__ G = (const g4 *)Gp;
     f32x4 *__restrict__ Wc = (f32x4 *)Wcp;
     const size_t n4 = N / 4, ld4 = ld / 4;
     constexpr size_t TILE = (size_t)GROUPS * 256;
@@ -111,7 +121,8 @@ __global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restric
         for (int i = 0; i < P; ++i) {
             const size_t row = (size_t)i * ld4;
             f32x4 w[GROUPS];
-            u16x4 g[GROUPS], v[GROUPS];
+            g4 g[GROUPS];
+            u16x4 v[GROUPS];
 #pragma unroll
             for (int q = 0; q < GROUPS; ++q) {
                 const size_t j = j0 + (size_t)q * 256;
@@ -130,7 +141,7 @@ __global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restric
                         float we = w[q][e];
                         unsigned short ve = 0;
                         if constexpr (MOM) ve = v[q][e];
-                        acc[q][e] += worker_rule_bf16<MOM>(we, ve, g[q][e], c[q][e], eta, rho, alpha, delta);
+                        acc[q][e] += worker_rule_bf16<MOM>(we, ve, grad_value(g[q][e]), c[q][e], eta, rho, alpha, delta);
                         w[q][e] = we;
                         if constexpr (MOM) v[q][e] = ve;
                     }
@@ -147,39 +158,38 @@ __global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restric
     }
     const size_t tail = N - n4 * 4;
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail)
-        scalar_param<MOM>(Wp, Vp, Gp, Wcp, P, n4 * 4 + threadIdx.x, ld, eta, rho, alpha, delta);
+        scalar_param<MOM, GT>(Wp, Vp, Gp, Wcp, P, n4 * 4 + threadIdx.x, ld, eta, rho, alpha, delta);
 }
 
 // Any alignment: one thread per parameter.
-template <bool MOM>
+template <bool MOM, typename GT>
 __global__ __launch_bounds__(256) void elastic_bf16_scalar_kernel(float *__restrict__ W, unsigned short *__restrict__ V,
-                                                                  const unsigned short *__restrict__ G,
+                                                                  const GT *__restrict__ G,
                                                                   float *__restrict__ Wc, int P, size_t N, size_t ld,
                                                                   float eta, float rho, float alpha, float delta)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += stride)
-        scalar_param<MOM>(W, V, G, Wc, P, j, ld, eta, rho, alpha, delta);
+        scalar_param<MOM, GT>(W, V, G, Wc, P, j, ld, eta, rho, alpha, delta);
 }
 
-template <bool MOM, bool NT>
-static void launch_bf16(int groups, dim3 grid, hipStream_t s, float *W, unsigned short *V, const unsigned short *G,
+template <bool MOM, bool NT, typename GT>
+static void launch_bf16(int groups, dim3 grid, hipStream_t s, float *W, unsigned short *V, const GT *G,
                         float *Wc, int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
 {
     switch (groups) {
-    case 1: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    case 2: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    default: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 1: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 1, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 2: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 2, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    default: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 4, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
     }
 }
 
 inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
 
-template <bool MOM>
-static int elastic_round_bf16(float *W, unsigned short *V, const unsigned short *G, float *Wc, int P, size_t N, size_t ld,
-                              float eta, float rho, float delta, void *stream)
+template <bool MOM, typename GT>
+static int elastic_round_bf16(const char *name, float *W, unsigned short *V, const GT *G, float *Wc, int P, size_t N,
+                              size_t ld, float eta, float rho, float delta, void *stream)
 {
-    const char *name = MOM ? "measgd_round_bf16" : "easgd_sync_round_bf16";
     if (!W || !G || !Wc || (MOM && !V)) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
     if (P < 1) return fail(EASGD_EINVAL, "%s: P must be >= 1, got %d", name, P);
     if (N == 0) return fail(EASGD_EINVAL, "%s: N must be >= 1", name);
@@ -189,7 +199,8 @@ static int elastic_round_bf16(float *W, unsigned short *V, const unsigned short 
     const Options &opt = options();
     hipStream_t s = static_cast<hipStream_t>(stream);
     const float alpha = eta * rho;
-    const bool vec = aligned16(W) && aligned16(Wc) && aligned8(G) && (!MOM || aligned8(V)) && (ld % 4 == 0);
+    const bool g_aligned = sizeof(GT) == 4 ? aligned16(G) : aligned8(G);
+    const bool vec = aligned16(W) && aligned16(Wc) && g_aligned && (!MOM || aligned8(V)) && (ld % 4 == 0);
     // fewer groups per thread for small N, so that the grid still covers the chip several times
     size_t groups = (size_t)opt.update_groups;
     while (groups > 1 && N / 4 / (groups * 256) < (size_t)(4 * num_cus())) groups /= 2;
@@ -202,11 +213,11 @@ static int elastic_round_bf16(float *W, unsigned short *V, const unsigned short 
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
     const dim3 grid((unsigned)blocks);
     if (!vec)
-        hipLaunchKernelGGL((elastic_bf16_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        hipLaunchKernelGGL((elastic_bf16_scalar_kernel<MOM, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     else if (opt.update_nontemporal)
-        launch_bf16<MOM, true>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        launch_bf16<MOM, true, GT>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     else
-        launch_bf16<MOM, false>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        launch_bf16<MOM, false, GT>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     return check_launch(name);
 }
 
@@ -217,13 +228,19 @@ extern "C" {
 int easgd_sync_round_bf16(float *W, const uint16_t *G, float *Wc, int P, size_t N, size_t ld,
                           float eta, float rho, void *stream)
 {
-    return easgd::elastic_round_bf16<false>(W, nullptr, G, Wc, P, N, ld, eta, rho, 0.0f, stream);
+    return easgd::elastic_round_bf16<false, uint16_t>("easgd_sync_round_bf16", W, nullptr, G, Wc, P, N, ld, eta, rho, 0.0f, stream);
 }
 
 int measgd_round_bf16(float *W, uint16_t *V, const uint16_t *G, float *Wc, int P, size_t N, size_t ld,
                       float eta, float rho, float delta, void *stream)
 {
-    return easgd::elastic_round_bf16<true>(W, V, G, Wc, P, N, ld, eta, rho, delta, stream);
+    return easgd::elastic_round_bf16<true, uint16_t>("measgd_round_bf16", W, V, G, Wc, P, N, ld, eta, rho, delta, stream);
+}
+
+int measgd_round_bf16v(float *W, uint16_t *V, const float *G, float *Wc, int P, size_t N, size_t ld,
+                       float eta, float rho, float delta, void *stream)
+{
+    return easgd::elastic_round_bf16<true, float>("measgd_round_bf16v", W, V, G, Wc, P, N, ld, eta, rho, delta, stream);
 }
 
 }  // extern "C"

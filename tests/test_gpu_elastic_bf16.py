@@ -118,6 +118,66 @@ def test_unaligned_operands_take_the_scalar_path(hip, momentum):
         assert (h[:s16] == PAD16).all() and (h[s16 + V16.size:] == PAD16).all()
 
 
+@pytest.mark.parametrize("P,N,ld", [(2, 3, 4), (9, 261, 264), (3, 4099, 4100), (8, 100_003, 100_004), (4, 1 << 22, 1 << 22),
+                                    (3, 1001, 1003)])
+def test_fp32_gradients_with_bf16_momentum(hip, P, N, ld):
+    """measgd_round_bf16v: only V is stored in 16 bits; the last shape takes the scalar path (ld % 4 != 0)."""
+    W, Wc = workloads.update_state(P, N, ld, seed=25)
+    G = workloads.update_gradients(P, N, 0, ld, seed=25)
+    V16 = narrow(workloads.update_gradients(P, N, 99, ld, seed=25, std=0.005))
+    dW, dWc, dG, dV = dev32(W), dev32(Wc), dev32(G), dev16(V16)
+    hip.measgd_round_bf16v(dW, dV, dG, dWc, float(ETA), float(RHO), float(DELTA), N=N)
+    Wv, V16v, Gv = W[:, :N].copy(), V16[:, :N].copy(), G[:, :N].copy()
+    oracle.measgd_round_bf16(Wv, V16v, Gv, Wc, ETA, RHO, DELTA)
+    W[:, :N] = Wv
+    V16[:, :N] = V16v
+    np.testing.assert_array_equal(host16(dV), V16)
+    assert normwise(to_host(dW), W) <= PER_ROUND_TOL
+    assert normwise(to_host(dWc), Wc) <= PER_ROUND_TOL
+    np.testing.assert_array_equal(to_host(dG), G)
+
+
+def test_training_rounds_with_bf16_momentum(hip):
+    """easgd_grad + measgd_round_bf16v over 30 rounds of a small MLP: the update of every round is checked against
+    the oracle on the gradient bits the GPU produced (the gradient itself has its own parity tests), and the
+    loss follows the run with fp32 momentum buffers."""
+    wl = workloads.WORKLOADS["cfg1"]
+    dims, P, b = list(wl.dims), wl.P, wl.batch
+    N = workloads.mlp_num_params(dims)
+    ld = workloads.round_up(N, 4)
+    w0 = workloads.init_packed_weights(wl)
+    W = workloads.replicate(w0, P, ld); Wc = w0.copy()
+    eta, rho, delta = 0.05, 0.1, 0.9
+    dW, dWc = dev32(W), dev32(Wc)
+    dW32, dWc32 = dev32(W), dev32(Wc)
+    dV16 = torch.zeros((P, ld), dtype=torch.bfloat16, device="cuda")
+    dV32 = torch.zeros((P, ld), dtype=torch.float32, device="cuda")
+    dG = torch.zeros((P, ld), dtype=torch.float32, device="cuda")
+    dloss = torch.zeros(P, dtype=torch.float32, device="cuda")
+    ws = torch.empty(hip.easgd_grad_workspace_bytes(dims, P, b), dtype=torch.uint8, device="cuda")
+    V16 = np.zeros((P, N), dtype=np.uint16)
+    Wh = np.ascontiguousarray(W[:, :N]); Wch = Wc.copy()
+    losses16, losses32 = [], []
+    X, y = workloads.minibatch(wl, 0)          # the same minibatch every round, so that the loss has to fall
+    dX, dy = dev32(X), torch.from_numpy(y).cuda()
+    for t in range(30):
+        hip.easgd_grad(dims, dW, dX, dy, dG, loss=dloss, workspace=ws)
+        losses16.append(float(dloss.mean()))
+        G = np.ascontiguousarray(to_host(dG)[:, :N])
+        hip.measgd_round_bf16v(dW, dV16, dG, dWc, eta, rho, delta, N=N)
+        # teacher-forced on the replicas the GPU had at the start of this round
+        oracle.measgd_round_bf16(Wh, V16, G, Wch, F(eta), F(rho), F(delta))
+        np.testing.assert_array_equal(host16(dV16)[:, :N], V16)
+        assert normwise(to_host(dW)[:, :N], Wh) <= PER_ROUND_TOL
+        assert normwise(to_host(dWc), Wch) <= PER_ROUND_TOL
+        Wh = np.ascontiguousarray(to_host(dW)[:, :N]); Wch = to_host(dWc).copy()
+        hip.easgd_grad(dims, dW32, dX, dy, dG, loss=dloss, workspace=ws)
+        losses32.append(float(dloss.mean()))
+        hip.measgd_round(dW32, dV32, dG, dWc32, eta, rho, delta, N=N)
+    assert losses16[-1] < 0.8 * losses16[0]                        # it trains
+    assert abs(losses16[-1] - losses32[-1]) < 0.02 * losses32[0]   # and tracks the fp32-momentum run
+
+
 def test_hundred_rounds_free_running(hip):
     P, N = 8, (1 << 18) + 3
     ld = workloads.round_up(N, 4)

@@ -211,3 +211,29 @@ def test_planted_mistake_is_caught(name):
         except AssertionError:
             failed.append(pin.__name__)
     assert failed, f"no pin notices the mistake '{name}'"
+
+
+def test_fp32_gradients_with_bf16_momentum():
+    """Only V stored in 16 bits: representable fp32 gradients give what their 16-bit patterns give; for other
+    gradients V stays within half a spacing of the fp32-storage oracle's and W carries exactly that rounding."""
+    rng = np.random.default_rng(9)
+    P, N = 4, 1031
+    W = rng.standard_normal((P, N)).astype(F); Wc = rng.standard_normal(N).astype(F)
+    V16 = ob.bf16_round((0.05 * rng.standard_normal((P, N))).astype(F))
+    G16 = ob.bf16_round(rng.standard_normal((P, N)).astype(F))
+    eta, rho, mu = 0.05, 0.3, 0.9
+    a = (W.copy(), V16.copy(), Wc.copy()); b = (W.copy(), V16.copy(), Wc.copy())
+    ob.measgd_round_bf16(a[0], a[1], G16, a[2], eta, rho, mu)
+    ob.measgd_round_bf16(b[0], b[1], ob.bf16_widen(G16).copy(), b[2], eta, rho, mu)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    G = rng.standard_normal((P, N)).astype(F)                      # not representable in 16 bits
+    W2, Wc2, V2 = W.copy(), Wc.copy(), ob.bf16_widen(V16).copy()
+    oracle.measgd_round(W2, V2, G, Wc2, eta, rho, mu)
+    W1, V1, Wc1 = W.copy(), V16.copy(), Wc.copy()
+    ob.measgd_round_bf16(W1, V1, G, Wc1, eta, rho, mu)
+    dv = ob.bf16_widen(V1).astype(np.float64) - V2
+    slop = 2.0 ** -22 * (np.abs(mu * ob.bf16_widen(V16)) + np.abs(eta * G))
+    assert np.all(np.abs(dv) <= 2.0 ** -8 * np.abs(V2) * (1 + 1e-6) + slop)
+    np.testing.assert_allclose(W1.astype(np.float64) - W2, dv, atol=3e-7)
+    assert np.array_equal(Wc1, Wc2)

@@ -63,6 +63,19 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert lib.easgd_sync_round(fake, fake, fake, 1, 8, 4, 0.1, 0.1, None) == -1
     assert b"ld" in lib.easgd_last_error()
     assert lib.measgd_round(fake, None, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+    # the bfloat16-storage forms validate the same way
+    lib.easgd_sync_round_bf16.argtypes = [vp, vp, vp, ctypes.c_int, sz, sz, f, f, vp]
+    for fn in (lib.measgd_round_bf16, lib.measgd_round_bf16v):
+        fn.argtypes = [vp, vp, vp, vp, ctypes.c_int, sz, sz, f, f, f, vp]
+        assert fn(fake, None, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+        assert b"NULL" in lib.easgd_last_error()
+        assert fn(fake, fake, fake, fake, 0, 4, 4, 0.1, 0.1, 0.9, None) == -1
+        assert fn(fake, fake, fake, fake, 1, 0, 4, 0.1, 0.1, 0.9, None) == -1
+        assert fn(fake, fake, fake, fake, 1, 8, 4, 0.1, 0.1, 0.9, None) == -1
+    assert b"measgd_round_bf16v: ld (4) < N (8)" in lib.easgd_last_error()
+    assert lib.easgd_sync_round_bf16(fake, None, fake, 1, 4, 4, 0.1, 0.1, None) == -1
+    assert lib.easgd_sync_round_bf16(fake, fake, fake, 1, 8, 4, 0.1, 0.1, None) == -1
+    assert b"easgd_sync_round_bf16" in lib.easgd_last_error()
     lib.sync_sgd_round.argtypes = [vp, vp, vp, ctypes.c_int, sz, sz, f, f, vp]
     assert lib.sync_sgd_round(None, None, fake, 1, 4, 4, 0.1, 0.0, None) == -1
     assert lib.sync_sgd_round(fake, None, None, 1, 4, 4, 0.1, 0.0, None) == -1

@@ -76,13 +76,16 @@ def _sum_ms(starts, stops):
 # GPU legs
 # ---------------------------------------------------------------------------
 
-def bench_training(hip, wl, steps, warmup, one_call=True):
+def bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=False):
+    """v_bf16: momentum buffers stored as bfloat16 (an extension; momentum workloads only)."""
     import torch
     ld = workloads.round_up(wl.N, 4)
     w0 = workloads.init_packed_weights(wl)
     dW = torch.from_numpy(workloads.replicate(w0, wl.P, ld)).cuda()
     dWc = torch.from_numpy(w0.copy()).cuda()
     dV = torch.zeros_like(dW) if wl.momentum else None
+    if v_bf16:
+        dV = torch.zeros(dW.shape, dtype=torch.bfloat16, device="cuda")
     dG = torch.zeros_like(dW)
     n_batches = min(wl.rounds, 16)
     batches = []
@@ -104,7 +107,9 @@ def bench_training(hip, wl, steps, warmup, one_call=True):
         hip.easgd_grad(wl.dims, dW, X, y, dG, None, workspace=ws)
         if ev:
             ev[1].record()
-        if wl.momentum:
+        if v_bf16:
+            hip.measgd_round_bf16v(dW, dV, dG, dWc, wl.eta, wl.rho, wl.delta, N=wl.N)
+        elif wl.momentum:
             hip.measgd_round(dW, dV, dG, dWc, wl.eta, wl.rho, wl.delta, N=wl.N)
         else:
             hip.easgd_sync_round(dW, dG, dWc, wl.eta, wl.rho, N=wl.N)
@@ -426,6 +431,19 @@ def main():
                             "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4),
                             "traffic": MEASURED_GRAD_TRAFFIC_BYTES.get(args.workload),
                             "useful_flops_per_launch": grad_flops(wl), "avg_launch_ms": round(r["grad_ms"], 4)}
+        if wl.momentum:
+            # an extension (the paper names low precision only as future work): the same rounds with the momentum
+            # buffers stored as bfloat16
+            b1 = bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=True)
+            b2 = bench_training(hip, wl, steps, warmup, one_call=False, v_bf16=True)
+            line["bf16_momentum_storage"] = {
+                "rounds_per_s": round(steps / b1["elapsed_s"], 2), "ms_per_step": round(b1["ms_per_step"], 4),
+                "two_call_path": {"rounds_per_s": round(steps / b2["elapsed_s"], 2),
+                                  "ms_per_step": round(b2["ms_per_step"], 4),
+                                  "phases_ms": {"easgd_grad": round(b2["grad_ms"], 4),
+                                                "elastic_update": round(b2["update_ms"], 4)}},
+                "note": "extension: easgd_mlp_round / measgd_round_bf16v with bfloat16 momentum buffers; "
+                        "fp32 replicas, center, gradients and arithmetic"}
         line["host_fed"] = bench_host_fed(hip, wl, steps, warmup)
         line["update_in_round"] = {"GBs_algorithmic": round(update_bytes(wl) / (r["update_ms"] * 1e-3) / 1e9, 1),
                                    "note": "replicas of this workload fit the 256 MB last-level cache only partly; "

@@ -10,6 +10,8 @@
  *                 measgd_round      the same with the momentum worker rule Eq. (5),(6)
  *   steps (1)-(5) easgd_mlp_round   the whole round in one call, the update fused into
  *                                   backward propagation
+ *   extension     *_bf16, *_bf16v   the same updates with gradients and/or momentum buffers
+ *                                   stored as bfloat16 (fp32 replicas, center and arithmetic)
  *
  * Conventions shared by every entry point
  *   - every pointer marked DEVICE is a device (HBM) pointer owned by the caller;
@@ -210,6 +212,19 @@ int easgd_mlp_round(const int *dims, int n_layers,
                     float *G, float *loss,
                     float eta, float rho, float delta,
                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * easgd_mlp_round with the momentum buffers stored as bfloat16 (an extension; format, rounding and the
+ * arithmetic of Eq. (5) as described for measgd_round_bf16v, the gradient being the fp32 value the
+ * matrix product has just accumulated).  V DEVICE in/out [P][ld] bfloat16, not NULL, 2-byte aligned.
+ * Results equal easgd_grad followed by measgd_round_bf16v.  Everything else as for easgd_mlp_round.
+ */
+int easgd_mlp_round_bf16v(const int *dims, int n_layers,
+                          float *W, uint16_t *V, float *Wc, size_t ld,
+                          const float *X, const int32_t *y, int P, int b,
+                          float *G, float *loss,
+                          float eta, float rho, float delta,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /* Number of parameters N of the packed layout for `dims`; 0 on invalid input. */
 size_t easgd_mlp_num_params(const int *dims, int n_layers);

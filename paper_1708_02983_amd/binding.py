@@ -62,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.easgd_mlp_round_workspace_bytes.restype = sz
     lib.easgd_mlp_round.argtypes = [ip, i, vp, vp, vp, sz, vp, vp, i, i, vp, vp, f, f, f, vp, sz, vp]
     lib.easgd_mlp_round.restype = i
+    lib.easgd_mlp_round_bf16v.argtypes = [ip, i, vp, vp, vp, sz, vp, vp, i, i, vp, vp, f, f, f, vp, sz, vp]
+    lib.easgd_mlp_round_bf16v.restype = i
     lib.easgd_mlp_num_params.argtypes = [ip, i]
     lib.easgd_mlp_num_params.restype = sz
     lib.easgd_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -219,7 +221,8 @@ def easgd_mlp_round_workspace_bytes(dims: Sequence[int], P: int, b: int) -> int:
 
 def easgd_mlp_round(dims: Sequence[int], W, Wc, X, y, eta: float, rho: float, V=None, delta: float = 0.0,
                     G=None, loss=None, workspace=None, stream=None):
-    """Steps (1)-(5) in one call, the update fused into backward propagation; V selects Eq. (5),(6);
+    """Steps (1)-(5) in one call, the update fused into backward propagation; V selects Eq. (5),(6)
+    (a torch.bfloat16 V selects the form that stores the momentum buffers in 16 bits, an extension);
     the gradients are stored only when G is given.  Returns the workspace used."""
     arr, L = _dims(dims)
     if W.dim() != 2 or X.dim() != 3 or y.dim() != 2:
@@ -237,8 +240,10 @@ def easgd_mlp_round(dims: Sequence[int], W, Wc, X, y, eta: float, rho: float, V=
     nbytes = easgd_mlp_round_workspace_bytes(dims, P, b)
     if workspace is None:
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
-    _check(_lib.easgd_mlp_round(arr, L, _dev("W", W, torch.float32, need),
-                                None if V is None else _dev("V", V, torch.float32, need),
+    v16 = V is not None and V.dtype == torch.bfloat16
+    entry = _lib.easgd_mlp_round_bf16v if v16 else _lib.easgd_mlp_round
+    _check(entry(arr, L, _dev("W", W, torch.float32, need),
+                                None if V is None else _dev("V", V, torch.bfloat16 if v16 else torch.float32, need),
                                 _dev("Wc", Wc, torch.float32, N), ld,
                                 _dev("X", X, torch.float32, P * b * dims[0]),
                                 _dev("y", y, torch.int32, P * b), P, b,

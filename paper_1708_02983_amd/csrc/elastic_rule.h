@@ -19,6 +19,43 @@ __device__ __forceinline__ T worker_rule(T &w, T &v, T g, T c, float eta, float 
     return d;
 }
 
+// ---- bfloat16 storage of gradients and momentum buffers (an extension; the paper keeps fp32 throughout) ----
+// bfloat16 = the upper 16 bits of an fp32.  Widening is exact.  Narrowing rounds to nearest, ties to even; beyond
+// the largest finite value it gives infinity; a NaN becomes 0x7FC0 with the input's sign.
+__device__ __forceinline__ float bf16_widen(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
+
+__device__ __forceinline__ unsigned short bf16_narrow(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)(((u >> 16) & 0x8000u) | 0x7fc0u);
+    // adds just under half a unit of the kept part, and one more if the kept part is odd: ties go to even
+    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// One worker's rule on one parameter whose momentum is stored as bfloat16 (g: the gradient as fp32).
+// Eq. (5) decides a stored code, so its arithmetic is pinned: fl(fl(delta*v) - fl(eta*g)), no fused
+// multiply-add, then narrowed; Eq. (6) adds V_{t+1} as stored.  Returns d = w - c (time-t values).
+template <bool MOM>
+__device__ __forceinline__ float worker_rule_bf16(float &w, unsigned short &v16, float g, float c,
+                                                  float eta, float rho, float alpha, float delta)
+{
+    const float d = w - c;
+    if constexpr (MOM) {
+        float cand;
+        {
+#pragma clang fp contract(off)
+            const float dv = delta * bf16_widen(v16);
+            const float eg = eta * g;
+            cand = dv - eg;                   // Eq. (5), each operation rounded on its own
+        }
+        v16 = bf16_narrow(cand);
+        w = (w + bf16_widen(v16)) - alpha * d;   // Eq. (6) with V_{t+1} as stored
+    } else {
+        w = w - eta * (g + rho * d);          // Eq. (1)
+    }
+    return d;
+}
+
 // Eq. (2) alone, ahead of the worker rules, for block `block` of 256 threads (T = float or a vector of 4 floats;
 // the last of n_blocks blocks also owns the N % 4 tail of the vector form):
 //   Wc[j] <- c + alpha * sum_i (W_i[j] - c)  with c = Wc[j], workers in ascending order (the order of the fused

@@ -5,51 +5,18 @@
 // N*(12P+8) (EASGD), N*(14P+8) instead of N*(20P+8) (momentum), N*(16P+8) when only the momentum
 // buffers are stored in 16 bits and the gradients arrive as fp32 (as easgd_grad writes them).
 //
-// bfloat16 = the upper 16 bits of an fp32.  Widening is exact.  Narrowing rounds to nearest, ties to
-// even; beyond the largest finite value it gives infinity; a NaN becomes 0x7FC0 with the input's sign.
-// Eq. (5) decides a stored code, so its arithmetic is pinned: fl(fl(delta*v) - fl(eta*g)), no fused
-// multiply-add, then narrowed; Eq. (6) adds the stored (narrowed) V_{t+1}.
+// The format, its rounding and the worker rule are in elastic_rule.h (worker_rule_bf16), shared with the
+// matrix-product epilogue of the whole-round call.
 //
 // Same skeleton as elastic_vec4_kernel: a block owns GROUPS*256 groups of four consecutive parameters
 // and walks the workers in ascending order (fixed summation order for Eq. (2)).
 #include "common.h"
+#include "elastic_rule.h"
 
 namespace easgd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float bf16_widen(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
-
-__device__ __forceinline__ unsigned short bf16_narrow(float x)
-{
-    const unsigned u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)(((u >> 16) & 0x8000u) | 0x7fc0u);
-    // adds just under half a unit of the kept part, and one more if the kept part is odd: ties go to even
-    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-
-// One worker's rule on one parameter.  Returns d = w - c (time-t values).
-template <bool MOM>
-__device__ __forceinline__ float worker_rule_bf16(float &w, unsigned short &v16, float g, float c,
-                                                  float eta, float rho, float alpha, float delta)
-{
-    const float d = w - c;
-    if constexpr (MOM) {
-        float cand;
-        {
-#pragma clang fp contract(off)
-            const float dv = delta * bf16_widen(v16);
-            const float eg = eta * g;
-            cand = dv - eg;                   // Eq. (5), each operation rounded on its own
-        }
-        v16 = bf16_narrow(cand);
-        w = (w + bf16_widen(v16)) - alpha * d;   // Eq. (6) with V_{t+1} as stored
-    } else {
-        w = w - eta * (g + rho * d);          // Eq. (1)
-    }
-    return d;
-}
 
 // A gradient element as fp32: GT = unsigned short (bfloat16 storage) or float.
 __device__ __forceinline__ float grad_value(unsigned short g) { return bf16_widen(g); }

@@ -30,7 +30,7 @@ enum { K_CONTIG = 0, MN_CONTIG = 1 };
 // EPI_ELASTIC / EPI_ELASTIC_MOM: the product is a gradient tile g; the epilogue applies the worker rule
 // Eq. (1) / Eq. (5),(6) to the matching tile of the replica (and momentum buffer) in place, with the
 // time-t center read from `center`; g itself is stored only when C is not null.
-enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_ELASTIC = 3, EPI_ELASTIC_MOM = 4 };
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_ELASTIC = 3, EPI_ELASTIC_MOM = 4, EPI_ELASTIC_MOM_BF16 = 5 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -57,6 +57,7 @@ struct GemmArgs {
     // elastic epilogues: replica / momentum tiles indexed like C (worker stride c_ws, row stride ldc);
     // the center has the row stride ldc and no worker stride
     float *Wt, *Vt;
+    unsigned short *Vt16;               // EPI_ELASTIC_MOM_BF16: the momentum tiles stored as bfloat16
     const float *center;
     float eta, rho, alpha, delta;
     // extra blocks at the end of the grid that run the center rule beside the product (bandwidth-bound
@@ -486,13 +487,15 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     // epilogue: accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
     // Addresses are split into a block-uniform row pointer (scalar arithmetic) and one 32-bit lane offset
     // that is computed once; tiles that lie fully inside C skip the per-element bounds checks.
-    constexpr bool ELASTIC = (EPI == EPI_ELASTIC || EPI == EPI_ELASTIC_MOM);
+    constexpr bool ELASTIC = (EPI == EPI_ELASTIC || EPI == EPI_ELASTIC_MOM || EPI == EPI_ELASTIC_MOM_BF16);
     constexpr bool MOM = (EPI == EPI_ELASTIC_MOM);
+    constexpr bool MOM16 = (EPI == EPI_ELASTIC_MOM_BF16);
     const bool keep = !ELASTIC || p.C != nullptr;                                     // uniform
     float *__restrict__ C = keep ? p.C + (size_t)w * p.c_ws + (size_t)split * p.c_ss : nullptr;
     const float *__restrict__ mask = (EPI == EPI_MASK) ? p.mask + (size_t)w * p.mask_ws : nullptr;
     float *__restrict__ Wr = ELASTIC ? p.Wt + (size_t)w * p.c_ws : nullptr;
     float *__restrict__ Vr = MOM ? p.Vt + (size_t)w * p.c_ws : nullptr;
+    unsigned short *__restrict__ Vr16 = MOM16 ? p.Vt16 + (size_t)w * p.c_ws : nullptr;
     const float *__restrict__ Cc = ELASTIC ? p.center : nullptr;
     const int wave_m = __builtin_amdgcn_readfirstlane(m0 + wm0), wave_n = __builtin_amdgcn_readfirstlane(n0 + wn0);
     const unsigned lane_c = (unsigned)(4 * frag_k) * (unsigned)p.ldc + (unsigned)frag_x;
@@ -505,20 +508,24 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                 const int n = wave_n + j * 32;                                        // uniform
                 if constexpr (ELASTIC) {
                     float wv[16], cv[16], vv[16];
+                    unsigned short v16[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {  // all loads of the tile first, so that they overlap
                         const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
                         wv[r] = (Wr + row)[lane_c];
                         cv[r] = (Cc + row)[lane_c];
                         vv[r] = MOM ? (Vr + row)[lane_c] : 0.f;
+                        v16[r] = MOM16 ? (Vr16 + row)[lane_c] : (unsigned short)0;
                     }
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
                         const float g = acc[i][j][r];
-                        worker_rule<MOM>(wv[r], vv[r], g, cv[r], p.eta, p.rho, p.alpha, p.delta);
+                        if constexpr (MOM16) worker_rule_bf16<true>(wv[r], v16[r], g, cv[r], p.eta, p.rho, p.alpha, p.delta);
+                        else worker_rule<MOM>(wv[r], vv[r], g, cv[r], p.eta, p.rho, p.alpha, p.delta);
                         (Wr + row)[lane_c] = wv[r];
                         if (MOM) (Vr + row)[lane_c] = vv[r];
+                        if (MOM16) (Vr16 + row)[lane_c] = v16[r];
                         if (keep) (C + row)[lane_c] = g;
                     }
                     continue;
@@ -554,7 +561,13 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                         const size_t at = (size_t)m * p.ldc + n;
                         if constexpr (ELASTIC) {
                             float wv = Wr[at], vv = MOM ? Vr[at] : 0.f;
-                            worker_rule<MOM>(wv, vv, v, Cc[at], p.eta, p.rho, p.alpha, p.delta);
+                            if constexpr (MOM16) {
+                                unsigned short v16 = Vr16[at];
+                                worker_rule_bf16<true>(wv, v16, v, Cc[at], p.eta, p.rho, p.alpha, p.delta);
+                                Vr16[at] = v16;
+                            } else {
+                                worker_rule<MOM>(wv, vv, v, Cc[at], p.eta, p.rho, p.alpha, p.delta);
+                            }
                             Wr[at] = wv;
                             if (MOM) Vr[at] = vv;
                             if (keep) C[at] = v;

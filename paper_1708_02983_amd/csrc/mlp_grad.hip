@@ -472,6 +472,7 @@ static bool forward_launch_has_room(int M, int N, int P, int splits)
 struct ElasticStep {
     float *W, *V, *Wc;
     float eta, rho, delta;
+    unsigned short *V16;    // momentum buffers stored as bfloat16 (then V is null), or null
 };
 
 static int grad_impl(const char *name, const int *dims, int n_layers, const float *W, size_t ld, const float *X,
@@ -543,8 +544,19 @@ int easgd_mlp_round(const int *dims, int n_layers, float *W, float *V, float *Wc
                     float eta, float rho, float delta, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!Wc) return easgd::fail(EASGD_EINVAL, "easgd_mlp_round: NULL pointer");
-    const easgd::ElasticStep step = {W, V, Wc, eta, rho, delta};
+    const easgd::ElasticStep step = {W, V, Wc, eta, rho, delta, nullptr};
     return easgd::grad_impl("easgd_mlp_round", dims, n_layers, W, ld, X, y, P, b, G, loss, workspace,
+                            workspace_bytes, stream, &step);
+}
+
+int easgd_mlp_round_bf16v(const int *dims, int n_layers, float *W, uint16_t *V, float *Wc, size_t ld,
+                          const float *X, const int32_t *y, int P, int b, float *G, float *loss,
+                          float eta, float rho, float delta, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Wc || !V) return easgd::fail(EASGD_EINVAL, "easgd_mlp_round_bf16v: NULL pointer");
+    if (reinterpret_cast<uintptr_t>(V) & 1u) return easgd::fail(EASGD_EINVAL, "easgd_mlp_round_bf16v: V must be 2-byte aligned");
+    const easgd::ElasticStep step = {W, nullptr, Wc, eta, rho, delta, V};
+    return easgd::grad_impl("easgd_mlp_round_bf16v", dims, n_layers, W, ld, X, y, P, b, G, loss, workspace,
                             workspace_bytes, stream, &step);
 }
 
@@ -674,14 +686,15 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     // The weight-gradient product of a layer is held back until the next product is known, because two
     // independent products can share a launch (launch_pair_*): with the input-gradient product of the layer
     // below when the held one is narrow, or with the weight-gradient product of the layer below.
-    const int epi = !step ? EPI_NONE : (step->V ? EPI_ELASTIC_MOM : EPI_ELASTIC);
+    const int epi = !step ? EPI_NONE : (step->V16 ? EPI_ELASTIC_MOM_BF16 : (step->V ? EPI_ELASTIC_MOM : EPI_ELASTIC));
     const bool pairing = options().gemm_pair != 0;
     const bool tile64 = options().gemm_tile == 0 || options().gemm_tile == 2;   // wide backward products use 64x64
     struct Held { bool have = false; GemmArgs a; bool vec = false; } held;
     auto launch_dw = [&](const GemmArgs &d, bool vec) {
         if (epi == EPI_NONE) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(d, vec, false, s);
         else if (epi == EPI_ELASTIC) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC>(d, vec, false, s);
-        else launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM>(d, vec, false, s);
+        else if (epi == EPI_ELASTIC_MOM) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM>(d, vec, false, s);
+        else launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM_BF16>(d, vec, false, s);
     };
     auto flush = [&]() {
         if (held.have) launch_dw(held.a, held.vec);
@@ -709,9 +722,12 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
                 } else if (epi == EPI_ELASTIC) {
                     if (held.vec) launch_pair_da_narrow_dw<EPI_ELASTIC, true>(a, held.a, s);
                     else launch_pair_da_narrow_dw<EPI_ELASTIC, false>(a, held.a, s);
-                } else {
+                } else if (epi == EPI_ELASTIC_MOM) {
                     if (held.vec) launch_pair_da_narrow_dw<EPI_ELASTIC_MOM, true>(a, held.a, s);
                     else launch_pair_da_narrow_dw<EPI_ELASTIC_MOM, false>(a, held.a, s);
+                } else {
+                    if (held.vec) launch_pair_da_narrow_dw<EPI_ELASTIC_MOM_BF16, true>(a, held.a, s);
+                    else launch_pair_da_narrow_dw<EPI_ELASTIC_MOM_BF16, false>(a, held.a, s);
                 }
                 held.have = false;
             } else {
@@ -732,6 +748,7 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         if (step) {
             d.Wt = step->W + pl.off[l];
             d.Vt = step->V ? step->V + pl.off[l] : nullptr;
+            d.Vt16 = step->V16 ? step->V16 + pl.off[l] : nullptr;
             d.center = center_t + pl.off[l];
             d.eta = step->eta; d.rho = step->rho; d.alpha = step->eta * step->rho; d.delta = step->delta;
         }
@@ -740,7 +757,8 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
             if (pairing && tile64 && held.vec && vec && held.a.N > 32 && d.N > 32) {
                 if (epi == EPI_NONE) launch_pair_dw_dw<EPI_NONE>(held.a, d, s);
                 else if (epi == EPI_ELASTIC) launch_pair_dw_dw<EPI_ELASTIC>(held.a, d, s);
-                else launch_pair_dw_dw<EPI_ELASTIC_MOM>(held.a, d, s);
+                else if (epi == EPI_ELASTIC_MOM) launch_pair_dw_dw<EPI_ELASTIC_MOM>(held.a, d, s);
+                else launch_pair_dw_dw<EPI_ELASTIC_MOM_BF16>(held.a, d, s);
                 held.have = false;
                 continue;
             }

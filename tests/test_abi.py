@@ -97,6 +97,12 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert b"NULL" in lib.easgd_last_error()
     assert lib.easgd_mlp_round(dims, 1, None, None, fake, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, big, None) == -1
     assert lib.easgd_mlp_round(dims, 1, fake, None, fake, 7000, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, big, None) == -1
+    lib.easgd_mlp_round_bf16v.argtypes = lib.easgd_mlp_round.argtypes
+    assert lib.easgd_mlp_round_bf16v(dims, 1, fake, None, fake, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.9, fake, big, None) == -1
+    assert b"easgd_mlp_round_bf16v: NULL" in lib.easgd_last_error()
+    assert lib.easgd_mlp_round_bf16v(dims, 1, fake, 0x1001, fake, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.9, fake, big, None) == -1
+    assert b"2-byte aligned" in lib.easgd_last_error()
+    assert lib.easgd_mlp_round_bf16v(dims, 1, fake, fake, fake, 7000, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.9, fake, big, None) == -1
     lib.easgd_grad_workspace_bytes.restype = ctypes.c_size_t
     short = lib.easgd_grad_workspace_bytes(dims, 1, 1, 1)     # enough for easgd_grad, not for the whole round
     assert lib.easgd_mlp_round(dims, 1, fake, None, fake, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, short, None) == -3

@@ -267,3 +267,66 @@ def test_cfg5_full_size_sampled(hip):
     assert normwise(to_host(dW[:, tidx]), W) <= HUNDRED_ROUND_TOL
     assert normwise(to_host(dWc[tidx]), Wc) <= HUNDRED_ROUND_TOL
     assert bool(torch.isfinite(dW).all()) and bool(torch.isfinite(dWc).all())
+
+
+# ---- the whole round in one call with bfloat16 momentum buffers --------------------------------------
+
+ROUND_CASES = [
+    ((5, 4, 3), 2, 3),
+    ((784, 10), 4, 64),
+    ((33, 17, 10), 3, 25),
+    ((50, 70, 30, 7), 9, 100),
+    ((784, 256, 128, 10), 3, 100),
+    ((512, 384, 10), 16, 128),
+    ((130, 1000), 2, 9),
+    ((784, 1024, 1024, 10), 16, 128),
+]
+
+
+@pytest.mark.parametrize("dims,P,b", ROUND_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_whole_round_with_bf16_momentum(hip, dims, P, b):
+    """easgd_mlp_round with a bfloat16 V against easgd_grad + measgd_round_bf16v (same bits for W, V and the
+    stored gradient) and against the oracle's rule on the gradient bits the GPU produced; two rounds, the second
+    from the state the first one left, with and without storing the gradient, and a local step (rho = 0)."""
+    eta, rho, delta = 0.05, 0.1, 0.9
+    N = workloads.mlp_num_params(dims)
+    wl = workloads.Workload("t", P=P, eta=eta, rho=rho, rounds=1, dims=tuple(dims), batch=b, N=N)
+    w0 = workloads.init_packed_weights(wl, seed=41)
+    ld = workloads.round_up(N, 4) + 4
+    rng = np.random.default_rng(41)
+    W = workloads.replicate(w0, P, ld)
+    W[:, :N] += (rng.standard_normal((P, N)) * 0.02).astype(F)
+    Wc = (w0 + (rng.standard_normal(N) * 0.01).astype(F)).astype(F)
+    V16 = np.full((P, ld), PAD16, dtype=np.uint16)
+    V16[:, :N] = oracle.bf16_round((rng.standard_normal((P, N)) * 0.002).astype(F))
+    rW, rWc, rV = dev32(W), dev32(Wc), dev16(V16)           # two calls
+    fW, fWc, fV = dev32(W), dev32(Wc), dev16(V16)           # one call
+    oW, oWc, oV = np.ascontiguousarray(W[:, :N]), Wc.copy(), np.ascontiguousarray(V16[:, :N])
+    rG = torch.full_like(rW, float("nan")); rloss = torch.empty(P, device="cuda")
+    for t, (keep_g, rho_t) in enumerate(((True, rho), (False, rho), (True, 0.0))):
+        X, y = workloads.minibatch(wl, t, seed=41)
+        dX, dy = dev32(X), torch.from_numpy(y).cuda()
+        hip.easgd_grad(dims, rW, dX, dy, rG, rloss)
+        G = to_host(rG)
+        if rho_t == 0.0:
+            c_before = to_host(rWc).copy()
+        hip.measgd_round_bf16v(rW, rV, rG, rWc, eta, rho_t, delta, N=N)
+        fG = torch.full_like(fW, float("nan")) if keep_g else None
+        floss = torch.empty(P, device="cuda")
+        hip.easgd_mlp_round(dims, fW, fWc, dX, dy, eta, rho_t, V=fV, delta=delta, G=fG, loss=floss)
+        what = f"round {t} keep_g={keep_g} rho={rho_t}"
+        if keep_g:
+            np.testing.assert_array_equal(to_host(fG), G, err_msg=what)
+        np.testing.assert_array_equal(to_host(floss), to_host(rloss), err_msg=what)
+        np.testing.assert_array_equal(host16(fV), host16(rV), err_msg=what)       # padding included
+        np.testing.assert_array_equal(to_host(fW), to_host(rW), err_msg=what)
+        assert normwise(to_host(fWc), to_host(rWc)) <= 1e-6, what
+        if rho_t == 0.0:
+            np.testing.assert_array_equal(to_host(fWc), c_before, err_msg=what)   # a local step leaves the center alone
+        # the oracle on the same gradient bits, from the state this round started with
+        oracle.measgd_round_bf16(oW, oV, np.ascontiguousarray(G[:, :N]), oWc, F(eta), F(rho_t), F(delta))
+        np.testing.assert_array_equal(host16(fV)[:, :N], oV, err_msg=what)
+        assert normwise(to_host(fW)[:, :N], oW) <= PER_ROUND_TOL, what
+        assert normwise(to_host(fWc), oWc) <= PER_ROUND_TOL, what
+        oW, oWc = np.ascontiguousarray(to_host(fW)[:, :N]), to_host(fWc).copy()
+    assert np.isnan(to_host(fW)[:, N:]).all()

@@ -390,7 +390,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P replicas live in one HBM); --gpus must be 1. "
-              "How the round would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+              "The design notes of this repository describe how the round would shard over several GPUs.", file=sys.stderr)
         sys.exit(2)
 
     import torch

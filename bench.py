@@ -76,8 +76,9 @@ def _sum_ms(starts, stops):
 # GPU legs
 # ---------------------------------------------------------------------------
 
-def bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=False):
-    """v_bf16: momentum buffers stored as bfloat16 (an extension; momentum workloads only)."""
+def bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=False, g_bf16=False):
+    """v_bf16: momentum buffers stored as bfloat16 (an extension; momentum workloads only); g_bf16: the two-call
+    path with the gradients stored as bfloat16 too (momentum workloads: together with v_bf16)."""
     import torch
     ld = workloads.round_up(wl.N, 4)
     w0 = workloads.init_packed_weights(wl)
@@ -86,7 +87,7 @@ def bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=False):
     dV = torch.zeros_like(dW) if wl.momentum else None
     if v_bf16:
         dV = torch.zeros(dW.shape, dtype=torch.bfloat16, device="cuda")
-    dG = torch.zeros_like(dW)
+    dG = torch.zeros(dW.shape, dtype=torch.bfloat16, device="cuda") if g_bf16 else torch.zeros_like(dW)
     n_batches = min(wl.rounds, 16)
     batches = []
     for t in range(n_batches):
@@ -107,7 +108,11 @@ def bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=False):
         hip.easgd_grad(wl.dims, dW, X, y, dG, None, workspace=ws)
         if ev:
             ev[1].record()
-        if v_bf16:
+        if g_bf16 and wl.momentum:
+            hip.measgd_round_bf16(dW, dV, dG, dWc, wl.eta, wl.rho, wl.delta, N=wl.N)
+        elif g_bf16:
+            hip.easgd_sync_round_bf16(dW, dG, dWc, wl.eta, wl.rho, N=wl.N)
+        elif v_bf16:
             hip.measgd_round_bf16v(dW, dV, dG, dWc, wl.eta, wl.rho, wl.delta, N=wl.N)
         elif wl.momentum:
             hip.measgd_round(dW, dV, dG, dWc, wl.eta, wl.rho, wl.delta, N=wl.N)
@@ -426,6 +431,13 @@ def main():
                                        "ms_per_step": round(r["ms_per_step"], 4),
                                        "phases_ms": {"easgd_grad": round(r["grad_ms"], 4),
                                                      "elastic_update": round(r["update_ms"], 4)}}})
+        # an extension: the two-call path with the gradients (and momentum buffers) stored as bfloat16
+        g = bench_training(hip, wl, steps, warmup, one_call=False, v_bf16=wl.momentum, g_bf16=True)
+        line["two_call_path"]["with_bf16_gradient_storage"] = {
+            "rounds_per_s": round(steps / g["elapsed_s"], 2), "ms_per_step": round(g["ms_per_step"], 4),
+            "phases_ms": {"easgd_grad": round(g["grad_ms"], 4), "elastic_update": round(g["update_ms"], 4)},
+            "note": "extension: easgd_grad writes bfloat16 gradients, the update reads them"
+                    + (" and keeps bfloat16 momentum buffers" if wl.momentum else "")}
         line["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all products of easgd_grad, two-call path)",
                             "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                             "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4),

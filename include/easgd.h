@@ -178,6 +178,19 @@ int easgd_grad(const int *dims, int n_layers,
                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * easgd_grad with the gradients stored as bfloat16 (an extension; format and rounding as described for
+ * measgd_round_bf16): every product is accumulated in fp32 exactly as in easgd_grad and narrowed once when it
+ * is stored, so G[i][j] here is the narrowed value of what easgd_grad writes.  G DEVICE out [P][ld] bfloat16,
+ * not NULL, 2-byte aligned (8-byte aligned if measgd_round_bf16 is to take its fast path on it).
+ * Everything else as for easgd_grad.
+ */
+int easgd_grad_bf16(const int *dims, int n_layers,
+                    const float *W, size_t ld,
+                    const float *X, const int32_t *y, int P, int b,
+                    uint16_t *G, float *loss,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * A whole Sync EASGD round in one call: steps (1)-(5) of Section 5.1 for the
  * multilayer perceptron of easgd_grad, with the elastic update fused into
  * backward propagation (the overlap of steps that Section 5.1 allows).

@@ -58,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.easgd_grad_workspace_bytes.restype = sz
     lib.easgd_grad.argtypes = [ip, i, vp, sz, vp, vp, i, i, vp, vp, vp, sz, vp]
     lib.easgd_grad.restype = i
+    lib.easgd_grad_bf16.argtypes = [ip, i, vp, sz, vp, vp, i, i, vp, vp, vp, sz, vp]
+    lib.easgd_grad_bf16.restype = i
     lib.easgd_mlp_round_workspace_bytes.argtypes = [ip, i, i, i]
     lib.easgd_mlp_round_workspace_bytes.restype = sz
     lib.easgd_mlp_round.argtypes = [ip, i, vp, vp, vp, sz, vp, vp, i, i, vp, vp, f, f, f, vp, sz, vp]
@@ -189,7 +191,8 @@ def easgd_grad_workspace_bytes(dims: Sequence[int], P: int, b: int) -> int:
 
 
 def easgd_grad(dims: Sequence[int], W, X, y, G, loss=None, workspace=None, stream=None):
-    """Step (1): gradients of all P workers into G[P][ld]; returns the workspace used."""
+    """Step (1): gradients of all P workers into G[P][ld]; returns the workspace used.
+    A torch.bfloat16 G selects the form that stores the gradients in 16 bits (an extension)."""
     arr, L = _dims(dims)
     if W.dim() != 2 or X.dim() != 3 or y.dim() != 2:
         raise ValueError("expected W[P][ld], X[P][b][d_in], y[P][b]")
@@ -204,10 +207,12 @@ def easgd_grad(dims: Sequence[int], W, X, y, G, loss=None, workspace=None, strea
     nbytes = easgd_grad_workspace_bytes(dims, P, b)
     if workspace is None:
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
-    _check(_lib.easgd_grad(arr, L, _dev("W", W, torch.float32, need), ld,
+    g16 = G.dtype == torch.bfloat16
+    entry = _lib.easgd_grad_bf16 if g16 else _lib.easgd_grad
+    _check(entry(arr, L, _dev("W", W, torch.float32, need), ld,
                            _dev("X", X, torch.float32, P * b * dims[0]),
                            _dev("y", y, torch.int32, P * b), P, b,
-                           _dev("G", G, torch.float32, need),
+                           _dev("G", G, torch.bfloat16 if g16 else torch.float32, need),
                            None if loss is None else _dev("loss", loss, torch.float32, P),
                            _dev("workspace", workspace, torch.uint8, nbytes), workspace.numel(),
                            _stream(stream)))

@@ -30,7 +30,9 @@ enum { K_CONTIG = 0, MN_CONTIG = 1 };
 // EPI_ELASTIC / EPI_ELASTIC_MOM: the product is a gradient tile g; the epilogue applies the worker rule
 // Eq. (1) / Eq. (5),(6) to the matching tile of the replica (and momentum buffer) in place, with the
 // time-t center read from `center`; g itself is stored only when C is not null.
-enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_ELASTIC = 3, EPI_ELASTIC_MOM = 4, EPI_ELASTIC_MOM_BF16 = 5 };
+// EPI_STORE_BF16: the product is narrowed to bfloat16 (round to nearest even) and stored at C16 instead of C.
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_ELASTIC = 3, EPI_ELASTIC_MOM = 4, EPI_ELASTIC_MOM_BF16 = 5,
+       EPI_STORE_BF16 = 6 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -38,6 +40,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 struct GemmArgs {
     const float *A, *B, *mask;
     float *C;
+    unsigned short *C16;                // EPI_STORE_BF16: the result as bfloat16, indexed like C
     size_t a_ws, b_ws, c_ws, mask_ws;   // worker strides (elements)
     size_t c_ss;                        // split stride of C (elements); split s writes C + s*c_ss
     int lda, ldb, ldc, ldmask;
@@ -490,8 +493,10 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     constexpr bool ELASTIC = (EPI == EPI_ELASTIC || EPI == EPI_ELASTIC_MOM || EPI == EPI_ELASTIC_MOM_BF16);
     constexpr bool MOM = (EPI == EPI_ELASTIC_MOM);
     constexpr bool MOM16 = (EPI == EPI_ELASTIC_MOM_BF16);
-    const bool keep = !ELASTIC || p.C != nullptr;                                     // uniform
+    constexpr bool OUT16 = (EPI == EPI_STORE_BF16);
+    const bool keep = !OUT16 && (!ELASTIC || p.C != nullptr);                         // uniform
     float *__restrict__ C = keep ? p.C + (size_t)w * p.c_ws + (size_t)split * p.c_ss : nullptr;
+    unsigned short *__restrict__ C16 = OUT16 ? p.C16 + (size_t)w * p.c_ws + (size_t)split * p.c_ss : nullptr;
     const float *__restrict__ mask = (EPI == EPI_MASK) ? p.mask + (size_t)w * p.mask_ws : nullptr;
     float *__restrict__ Wr = ELASTIC ? p.Wt + (size_t)w * p.c_ws : nullptr;
     float *__restrict__ Vr = MOM ? p.Vt + (size_t)w * p.c_ws : nullptr;
@@ -544,7 +549,8 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                     float v = acc[i][j][r];
                     if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
                     if (EPI == EPI_MASK) v = (gate[r] > 0.f) ? v : 0.f;
-                    (C + (size_t)m * p.ldc + n)[lane_c] = v;
+                    if constexpr (OUT16) (C16 + (size_t)m * p.ldc + n)[lane_c] = bf16_narrow(v);
+                    else (C + (size_t)m * p.ldc + n)[lane_c] = v;
                 }
             }
     } else {
@@ -574,7 +580,8 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                         } else {
                             if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
                             if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
-                            C[at] = v;
+                            if constexpr (OUT16) C16[at] = bf16_narrow(v);
+                            else C[at] = v;
                         }
                     }
                 }

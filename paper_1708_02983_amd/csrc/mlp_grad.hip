@@ -477,7 +477,7 @@ struct ElasticStep {
 
 static int grad_impl(const char *name, const int *dims, int n_layers, const float *W, size_t ld, const float *X,
                      const int32_t *y, int P, int b, float *G, float *loss, void *workspace, size_t workspace_bytes,
-                     void *stream, const ElasticStep *step);
+                     void *stream, const ElasticStep *step, unsigned short *G16 = nullptr);
 
 // A second stream per device (default priority) with the two events that order it against the caller's
 // stream: `fork` is recorded on the caller's stream when the round starts, `join` on the second stream when
@@ -539,6 +539,15 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
                             stream, nullptr);
 }
 
+int easgd_grad_bf16(const int *dims, int n_layers, const float *W, size_t ld, const float *X, const int32_t *y,
+                    int P, int b, uint16_t *G, float *loss, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!G) return easgd::fail(EASGD_EINVAL, "easgd_grad_bf16: NULL pointer");
+    if (reinterpret_cast<uintptr_t>(G) & 1u) return easgd::fail(EASGD_EINVAL, "easgd_grad_bf16: G must be 2-byte aligned");
+    return easgd::grad_impl("easgd_grad_bf16", dims, n_layers, W, ld, X, y, P, b, nullptr, loss, workspace,
+                            workspace_bytes, stream, nullptr, G);
+}
+
 int easgd_mlp_round(const int *dims, int n_layers, float *W, float *V, float *Wc, size_t ld,
                     const float *X, const int32_t *y, int P, int b, float *G, float *loss,
                     float eta, float rho, float delta, void *workspace, size_t workspace_bytes, void *stream)
@@ -566,11 +575,11 @@ namespace easgd {
 
 static int grad_impl(const char *name, const int *dims, int n_layers, const float *W, size_t ld, const float *X,
                      const int32_t *y, int P, int b, float *G, float *loss, void *workspace, size_t workspace_bytes,
-                     void *stream, const ElasticStep *step)
+                     void *stream, const ElasticStep *step, unsigned short *G16)
 {
     const int L = n_layers;
     GradPlan pl;
-    if (!W || !X || !y || (!G && !step)) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
+    if (!W || !X || !y || (!G && !G16 && !step)) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
     if (!make_plan(dims, L, P, b, pl))
         return fail(EASGD_EINVAL, "%s: need 1 <= n_layers <= %d, all dims >= 1, P >= 1, b >= 1", name, MAX_LAYERS);
     if (dims[L] > MAX_CLASSES) return fail(EASGD_EINVAL, "%s: at most %d classes, got %d", name, MAX_CLASSES, dims[L]);
@@ -686,12 +695,13 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
     // The weight-gradient product of a layer is held back until the next product is known, because two
     // independent products can share a launch (launch_pair_*): with the input-gradient product of the layer
     // below when the held one is narrow, or with the weight-gradient product of the layer below.
-    const int epi = !step ? EPI_NONE : (step->V16 ? EPI_ELASTIC_MOM_BF16 : (step->V ? EPI_ELASTIC_MOM : EPI_ELASTIC));
+    const int epi = !step ? (G16 ? EPI_STORE_BF16 : EPI_NONE) : (step->V16 ? EPI_ELASTIC_MOM_BF16 : (step->V ? EPI_ELASTIC_MOM : EPI_ELASTIC));
     const bool pairing = options().gemm_pair != 0;
     const bool tile64 = options().gemm_tile == 0 || options().gemm_tile == 2;   // wide backward products use 64x64
     struct Held { bool have = false; GemmArgs a; bool vec = false; } held;
     auto launch_dw = [&](const GemmArgs &d, bool vec) {
         if (epi == EPI_NONE) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(d, vec, false, s);
+        else if (epi == EPI_STORE_BF16) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_STORE_BF16>(d, vec, false, s);
         else if (epi == EPI_ELASTIC) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC>(d, vec, false, s);
         else if (epi == EPI_ELASTIC_MOM) launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM>(d, vec, false, s);
         else launch_gemm<MN_CONTIG, MN_CONTIG, EPI_ELASTIC_MOM_BF16>(d, vec, false, s);
@@ -719,6 +729,9 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
                 if (epi == EPI_NONE) {
                     if (held.vec) launch_pair_da_narrow_dw<EPI_NONE, true>(a, held.a, s);
                     else launch_pair_da_narrow_dw<EPI_NONE, false>(a, held.a, s);
+                } else if (epi == EPI_STORE_BF16) {
+                    if (held.vec) launch_pair_da_narrow_dw<EPI_STORE_BF16, true>(a, held.a, s);
+                    else launch_pair_da_narrow_dw<EPI_STORE_BF16, false>(a, held.a, s);
                 } else if (epi == EPI_ELASTIC) {
                     if (held.vec) launch_pair_da_narrow_dw<EPI_ELASTIC, true>(a, held.a, s);
                     else launch_pair_da_narrow_dw<EPI_ELASTIC, false>(a, held.a, s);
@@ -743,6 +756,7 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         d.A = act(l); d.a_ws = (size_t)b * d_in; d.lda = d_in; d.a_lim = d_in; d.a_ones = d_in;
         d.B = dz_l; d.b_ws = (size_t)b * d_out; d.ldb = d_out;
         d.C = G ? G + pl.off[l] : nullptr; d.c_ws = ld; d.ldc = d_out;
+        d.C16 = G16 ? G16 + pl.off[l] : nullptr;
         d.M = d_in + 1; d.N = d_out; d.K = b; d.P = P;
         d.splits = 1; d.k_per_split = (d.K + 63) / 64 * 64;
         if (step) {
@@ -756,6 +770,7 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         if (held.have) {     // two weight-gradient products in a row (no input-gradient product for layer 0)
             if (pairing && tile64 && held.vec && vec && held.a.N > 32 && d.N > 32) {
                 if (epi == EPI_NONE) launch_pair_dw_dw<EPI_NONE>(held.a, d, s);
+                else if (epi == EPI_STORE_BF16) launch_pair_dw_dw<EPI_STORE_BF16>(held.a, d, s);
                 else if (epi == EPI_ELASTIC) launch_pair_dw_dw<EPI_ELASTIC>(held.a, d, s);
                 else if (epi == EPI_ELASTIC_MOM) launch_pair_dw_dw<EPI_ELASTIC_MOM>(held.a, d, s);
                 else launch_pair_dw_dw<EPI_ELASTIC_MOM_BF16>(held.a, d, s);

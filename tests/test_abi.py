@@ -91,6 +91,12 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert lib.easgd_grad(dims, 0, fake, 7850, fake, fake, 1, 1, fake, None, fake, 1 << 30, None) == -1
     assert lib.easgd_grad(dims, 1, fake, 7850, fake, fake, 1, 1, fake, None, None, 0, None) == -3          # workspace
     assert lib.easgd_grad(dims, 1, fake, 7850, fake, fake, 1, 1, fake, None, 0x1000, 16, None) == -3
+    lib.easgd_grad_bf16.argtypes = lib.easgd_grad.argtypes
+    assert lib.easgd_grad_bf16(dims, 1, fake, 7850, fake, fake, 1, 1, None, None, fake, 1 << 30, None) == -1
+    assert b"easgd_grad_bf16: NULL" in lib.easgd_last_error()
+    assert lib.easgd_grad_bf16(dims, 1, fake, 7850, fake, fake, 1, 1, 0x1001, None, fake, 1 << 30, None) == -1
+    assert lib.easgd_grad_bf16(dims, 1, fake, 7000, fake, fake, 1, 1, fake, None, fake, 1 << 30, None) == -1
+    assert lib.easgd_grad_bf16(dims, 1, fake, 7850, fake, fake, 1, 1, fake, None, None, 0, None) == -3
     lib.easgd_mlp_round.argtypes = [ip, ctypes.c_int, vp, vp, vp, sz, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp, f, f, f, vp, sz, vp]
     big = 1 << 30
     assert lib.easgd_mlp_round(dims, 1, fake, None, None, 7850, fake, fake, 1, 1, None, None, 0.1, 0.1, 0.0, fake, big, None) == -1

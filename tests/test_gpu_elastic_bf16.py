@@ -330,3 +330,40 @@ def test_whole_round_with_bf16_momentum(hip, dims, P, b):
         assert normwise(to_host(fWc), oWc) <= PER_ROUND_TOL, what
         oW, oWc = np.ascontiguousarray(to_host(fW)[:, :N]), to_host(fWc).copy()
     assert np.isnan(to_host(fW)[:, N:]).all()
+
+
+GRAD_CASES = [((5, 4, 3), 2, 3), ((784, 10), 4, 64), ((33, 17, 10), 3, 25), ((50, 70, 30, 7), 9, 100),
+              ((784, 256, 128, 10), 3, 100), ((130, 1000), 2, 9), ((784, 1024, 1024, 10), 16, 128)]
+
+
+@pytest.mark.parametrize("dims,P,b", GRAD_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_gradient_stored_as_bf16_is_the_narrowed_fp32_gradient(hip, dims, P, b):
+    """easgd_grad with a bfloat16 G: the same accumulators as the fp32 form (which has its own parity tests against
+    the oracle), narrowed once: bit for bit the oracle's narrowing of the fp32 result; then one update from it."""
+    N = workloads.mlp_num_params(dims)
+    wl = workloads.Workload("t", P=P, eta=0.05, rho=0.1, rounds=1, dims=tuple(dims), batch=b, N=N)
+    w0 = workloads.init_packed_weights(wl, seed=43)
+    ld = workloads.round_up(N, 4) + 4
+    rng = np.random.default_rng(43)
+    W = workloads.replicate(w0, P, ld)
+    W[:, :N] += (rng.standard_normal((P, N)) * 0.02).astype(F)
+    X, y = workloads.minibatch(wl, 0, seed=43)
+    dW, dX, dy = dev32(W), dev32(X), torch.from_numpy(y).cuda()
+    G32 = torch.full_like(dW, float("nan")); l32 = torch.empty(P, device="cuda")
+    hip.easgd_grad(dims, dW, dX, dy, G32, l32)
+    G16 = torch.full((P, ld), float("nan"), dtype=torch.bfloat16, device="cuda"); l16 = torch.empty(P, device="cuda")
+    hip.easgd_grad(dims, dW, dX, dy, G16, l16)
+    want = np.full((P, ld), PAD16, dtype=np.uint16)
+    want[:, :N] = oracle.bf16_round(to_host(G32)[:, :N])
+    np.testing.assert_array_equal(host16(G16), want)              # padding untouched
+    np.testing.assert_array_equal(to_host(l16), to_host(l32))
+    # and the update that consumes it
+    Wc = w0.copy()
+    V16 = np.zeros((P, ld), dtype=np.uint16)
+    dWc, dV = dev32(Wc), dev16(V16)
+    hip.measgd_round_bf16(dW, dV, G16, dWc, 0.05, 0.1, 0.9, N=N)
+    oW, oV = np.ascontiguousarray(W[:, :N]), np.ascontiguousarray(V16[:, :N])
+    oracle.measgd_round_bf16(oW, oV, np.ascontiguousarray(want[:, :N]), Wc, F(0.05), F(0.1), F(0.9))
+    np.testing.assert_array_equal(host16(dV)[:, :N], oV)
+    assert normwise(to_host(dW)[:, :N], oW) <= PER_ROUND_TOL
+    assert normwise(to_host(dWc), Wc) <= PER_ROUND_TOL

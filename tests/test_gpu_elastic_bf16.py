@@ -269,6 +269,30 @@ def test_cfg5_full_size_sampled(hip):
     assert bool(torch.isfinite(dW).all()) and bool(torch.isfinite(dWc).all())
 
 
+def test_cfg4_full_size_sampled(hip):
+    """P = 8 x 61 M with bfloat16 G (Eq. (1)): the GPU runs every column, the oracle the sampled ones."""
+    wl = workloads.WORKLOADS["cfg4"]
+    P, N = wl.P, wl.N
+    eta, rho = F(wl.eta), F(wl.rho)
+    idx = workloads.sample_columns(N)
+    tidx = torch.from_numpy(idx).cuda()
+    dW = workloads.device_normal((P, N), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 1)
+    dWc = workloads.device_normal((N,), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 2)
+    W = to_host(dW[:, tidx]).copy(); Wc = to_host(dWc[tidx]).copy()
+    for t in range(10):
+        dG = workloads.device_normal((P, N), workloads.GRADIENT_STD, workloads.DEFAULT_SEED, 100 + t).to(torch.bfloat16)
+        G16 = host16(dG[:, tidx].contiguous()).copy()
+        hip.easgd_sync_round_bf16(dW, dG, dWc, float(eta), float(rho))
+        oracle.easgd_round_bf16(W, G16, Wc, eta, rho)
+        if t == 0:
+            assert normwise(to_host(dW[:, tidx]), W) <= PER_ROUND_TOL
+            assert normwise(to_host(dWc[tidx]), Wc) <= PER_ROUND_TOL
+        del dG
+    assert normwise(to_host(dW[:, tidx]), W) <= HUNDRED_ROUND_TOL
+    assert normwise(to_host(dWc[tidx]), Wc) <= HUNDRED_ROUND_TOL
+    assert bool(torch.isfinite(dW).all()) and bool(torch.isfinite(dWc).all())
+
+
 # ---- the whole round in one call with bfloat16 momentum buffers --------------------------------------
 
 ROUND_CASES = [

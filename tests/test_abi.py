@@ -15,7 +15,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libeasgd_hip.so
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "easgd.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:m?easgd)_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:m?easgd|sync_sgd)_[a-z0-9_]+)\s*\(", text)))
 
 
 @pytest.fixture(scope="module")
@@ -27,7 +27,9 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"easgd_sync_round", "measgd_round", "easgd_grad", "easgd_grad_workspace_bytes",
             "easgd_mlp_num_params", "easgd_last_error", "easgd_version", "easgd_set_option",
-            "easgd_get_option", "easgd_stream_copy", "easgd_stream_triad"} <= set(names)
+            "easgd_get_option", "easgd_stream_copy", "easgd_stream_triad", "easgd_mlp_round", "easgd_mlp_round_bf16v",
+            "easgd_mlp_round_workspace_bytes", "easgd_sync_round_bf16", "measgd_round_bf16", "measgd_round_bf16v",
+            "easgd_grad_bf16", "sync_sgd_round"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/easgd.h but not exported"
 

@@ -1,11 +1,13 @@
 """Rounds fed from pinned host memory through the double-buffered feeder (the data copy of the next round
-overlaps the current round, Algorithm 3) must give the same bits as rounds whose data is already resident."""
+overlaps the current round, Algorithm 3; the overlap of Sync EASGD3, Section 6.1.3): every fed round against the
+oracle's round, and the fed rounds against rounds whose data is already resident (the same bits)."""
 import numpy as np
 import pytest
 import torch
 
+import oracle
 import workloads
-from gpu_util import to_dev, to_host
+from gpu_util import HUNDRED_ROUND_TOL, PER_ROUND_TOL, match_gradients_all_workers, normwise, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 F = np.float32
@@ -21,9 +23,11 @@ def test_host_fed_rounds_equal_resident_rounds():
     W0 = workloads.replicate(w0, P, ld)
     batches = [workloads.minibatch(wl, t) for t in range(rounds)]
 
-    def run(feed):
+    def run(feed, snapshots=None):
         W, Wc = to_dev(W0), to_dev(w0.copy())
         V = torch.zeros_like(W)
+        V[:, N:] = float("nan")
+        G = torch.full_like(W, float("nan")) if snapshots is not None else None
         ws = torch.empty(hip.easgd_mlp_round_workspace_bytes(dims, P, b), dtype=torch.uint8, device="cuda")
         if not feed:
             for X, y in batches:
@@ -36,8 +40,10 @@ def test_host_fed_rounds_equal_resident_rounds():
                 if t + 1 < rounds:
                     feeder.submit((t + 1) % 2, *host[t + 1])      # copy of round t+1 runs beside round t
                 X, y = feeder.acquire(t % 2)
-                hip.easgd_mlp_round(dims, W, Wc, X, y, wl.eta, wl.rho, V=V, delta=wl.delta, workspace=ws)
+                hip.easgd_mlp_round(dims, W, Wc, X, y, wl.eta, wl.rho, V=V, delta=wl.delta, G=G, workspace=ws)
                 feeder.release(t % 2)
+                if snapshots is not None:      # device-side copies queued behind the round, read after the loop
+                    snapshots.append((W.clone(), V.clone(), Wc.clone(), G.clone()))
         torch.cuda.synchronize()
         return to_host(W), to_host(V), to_host(Wc)
 
@@ -46,7 +52,30 @@ def test_host_fed_rounds_equal_resident_rounds():
         got = run(True)
         for a, c in zip(ref, got):
             np.testing.assert_array_equal(a, c, err_msg=f"attempt {attempt}")
-    assert np.isfinite(ref[2]).all() and not np.array_equal(ref[2], w0)
+    assert np.isfinite(ref[2][:N]).all() and not np.array_equal(ref[2], w0)
+
+    # the fed rounds against the oracle (Algorithm 3 with the five steps of Section 5.1; Eq. (5),(6),(2)):
+    # teacher-forced (the oracle's round from the state the fed path held before round t) and free-running
+    snaps = []
+    kept = run(True, snaps)
+    for a, c in zip(ref, kept):
+        np.testing.assert_array_equal(a, c)             # keeping the gradient changes nothing else
+    V0 = np.zeros_like(W0); V0[:, N:] = np.nan
+    W, V, Wc = W0.copy(), V0.copy(), w0.copy()           # free-running oracle state
+    pW, pV, pWc = W0.copy(), V0.copy(), w0.copy()        # the fed path's state before round t
+    worst = 0.0
+    for t, (X, y) in enumerate(batches):
+        gW, gV, gWc, gG = (to_host(a) for a in snaps[t])
+        Gf, _, _ = match_gradients_all_workers(gG, dims, pW, X, y, PER_ROUND_TOL)
+        oracle.measgd_round(pW, pV, Gf, pWc, F(wl.eta), F(wl.rho), F(wl.delta), N=N)
+        worst = max(worst, normwise(gW, pW), normwise(gV, pV), normwise(gWc, pWc))
+        pW, pV, pWc = gW.copy(), gV.copy(), gWc.copy()
+        G, _ = oracle.mlp_grad_all_workers(dims, W, X, y)
+        oracle.measgd_round(W, V, G, Wc, F(wl.eta), F(wl.rho), F(wl.delta), N=N)
+    print(f"host-fed rounds against the oracle: teacher-forced worst {worst:.2e}; after {rounds} free-running rounds "
+          f"W {normwise(kept[0], W):.2e} V {normwise(kept[1], V):.2e} Wc {normwise(kept[2], Wc):.2e}")
+    assert worst <= PER_ROUND_TOL
+    assert max(normwise(kept[0], W), normwise(kept[1], V), normwise(kept[2], Wc)) <= HUNDRED_ROUND_TOL
 
 
 def test_feeder_rejects_pageable_memory_and_wrong_shapes():

@@ -49,7 +49,7 @@ def _gpu_round(hip, wl, dW, dV, dWc, dG, dX, dy, ws, path):
 
 
 @pytest.mark.parametrize("path", ["two_calls", "one_call"])
-@pytest.mark.parametrize("name,rounds,forced_every", [("cfg1", 10, 1), ("cfg2", 50, 10), ("cfg3", 20, 10)])
+@pytest.mark.parametrize("name,rounds,forced_every", [("cfg1", 10, 1), ("cfg2", 50, 1), ("cfg3", 20, 2)])
 def test_training_rounds(hip, name, rounds, forced_every, path):
     wl = workloads.WORKLOADS[name]
     assert rounds == wl.rounds
@@ -96,3 +96,55 @@ def test_training_rounds(hip, name, rounds, forced_every, path):
     if wl.momentum:
         assert normwise(to_host(dV), V) <= HUNDRED_ROUND_TOL
     assert np.isfinite(losses).all()
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+def test_the_call_the_benchmark_times(hip, name):
+    """The configuration the benchmark times: one easgd_mlp_round at the workload's full shape that stores no
+    gradient (G = NULL), under the library's default options (center rule placed per call, die-interleaved block
+    order, shared launches, single-launch head).  From a state a few rounds into training (replicas apart, a
+    center of its own, non-zero momentum) it must give the bits of the same call with the gradient kept, and
+    match the oracle's round, whose gate ties are resolved against that kept gradient."""
+    wl = workloads.WORKLOADS[name]
+    for opt, default in ((hip.OPT_ROUND_OVERLAP, 1), (hip.OPT_GEMM_XCD, 1), (hip.OPT_GEMM_PAIR, 1),
+                         (hip.OPT_MLP_HEAD, 1), (hip.OPT_GEMM_TILE, 0)):
+        assert hip.get_option(opt) == default
+    N, P = wl.N, wl.P
+    ld = workloads.round_up(N, 4)
+    w0 = workloads.init_packed_weights(wl)
+    rng = np.random.default_rng(77)
+    W = workloads.replicate(w0, P, ld)
+    for i in range(P):
+        W[i, :N] += rng.standard_normal(N, dtype=F) * F(0.004)
+    Wc = w0 + rng.standard_normal(N, dtype=F) * F(0.002)
+    V = np.full_like(W, np.nan)
+    for i in range(P):
+        V[i, :N] = rng.standard_normal(N, dtype=F) * F(1e-3)
+    X, y = workloads.minibatch(wl, 3)
+    dX, dy = to_dev(X), to_dev(y)
+    ws = torch.empty(hip.easgd_mlp_round_workspace_bytes(wl.dims, P, wl.batch), dtype=torch.uint8, device="cuda")
+    out = []
+    for keep in (False, True):
+        dW, dWc, dV = to_dev(W), to_dev(Wc), to_dev(V)
+        dG = torch.full_like(dW, float("nan")) if keep else None
+        dloss = torch.empty(P, device="cuda")
+        hip.easgd_mlp_round(wl.dims, dW, dWc, dX, dy, wl.eta, wl.rho, V=dV if wl.momentum else None,
+                            delta=wl.delta or 0.0, G=dG, loss=dloss, workspace=ws)
+        out.append((to_host(dW), to_host(dWc), to_host(dV), to_host(dloss)))
+        if keep:
+            G_gpu = to_host(dG)
+    for a, c in zip(out[0], out[1]):
+        np.testing.assert_array_equal(a, c)                    # storing the gradient changes nothing else
+    G, loss, ties = match_gradients_all_workers(G_gpu, wl.dims, W, X, y, PER_ROUND_TOL)
+    oW, oV, oWc = W.copy(), V.copy(), Wc.copy()
+    _oracle_update(wl, oW, oV, oWc, G)
+    gW, gWc, gV, gloss = out[0]
+    errs = {"W": normwise(gW, oW), "Wc": normwise(gWc, oWc)}
+    if wl.momentum:
+        errs["V"] = normwise(gV, oV)
+    else:
+        np.testing.assert_array_equal(gV, V)
+    print(f"{name} as timed (G=NULL, default options): {ties} gate tie(s), errors {errs}")
+    assert max(errs.values()) <= PER_ROUND_TOL
+    np.testing.assert_allclose(gloss, loss, rtol=1e-5)
+    assert not np.array_equal(gWc, Wc)

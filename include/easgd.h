@@ -178,6 +178,28 @@ int easgd_grad(const int *dims, int n_layers,
                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * easgd_grad for callers that cannot allocate device memory or hand over a workspace: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is an
+ * array of EASGD_STATIC_SCRATCH_BYTES bytes in the library's own device image: every GPU the library runs
+ * on holds one copy of it from the first use of the library on that GPU until the process ends.  The call
+ * itself allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine); its first
+ * call on a device looks up the device address of that array (hipGetSymbolAddress) and keeps it.
+ *
+ * Same arguments, kernels, results (bit for bit) and errors as easgd_grad, without `workspace` and
+ * `workspace_bytes`.  A shape whose easgd_grad_workspace_bytes(...) exceeds EASGD_STATIC_SCRATCH_BYTES is
+ * rejected with EASGD_EWORKSPACE before anything is launched (use easgd_grad then).  The array keeps the
+ * contents of the last call; nothing in it has to start at zero, every part is written before it is read.
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (different
+ * streams, or different host threads) race on it and must be serialised by the caller.
+ */
+#define EASGD_STATIC_SCRATCH_BYTES (64u << 20)
+
+int easgd_grad_static(const int *dims, int n_layers,
+                      const float *W, size_t ld,
+                      const float *X, const int32_t *y, int P, int b,
+                      float *G, float *loss, void *stream);
+
+/*
  * easgd_grad with the gradients stored as bfloat16 (an extension; format and rounding as described for
  * measgd_round_bf16): every product is accumulated in fp32 exactly as in easgd_grad and narrowed once when it
  * is stored, so G[i][j] here is the narrowed value of what easgd_grad writes.  G DEVICE out [P][ld] bfloat16,

@@ -58,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.easgd_grad_workspace_bytes.restype = sz
     lib.easgd_grad.argtypes = [ip, i, vp, sz, vp, vp, i, i, vp, vp, vp, sz, vp]
     lib.easgd_grad.restype = i
+    lib.easgd_grad_static.argtypes = [ip, i, vp, sz, vp, vp, i, i, vp, vp, vp]
+    lib.easgd_grad_static.restype = i
     lib.easgd_grad_bf16.argtypes = [ip, i, vp, sz, vp, vp, i, i, vp, vp, vp, sz, vp]
     lib.easgd_grad_bf16.restype = i
     lib.easgd_mlp_round_workspace_bytes.argtypes = [ip, i, i, i]
@@ -217,6 +219,31 @@ def easgd_grad(dims: Sequence[int], W, X, y, G, loss=None, workspace=None, strea
                            _dev("workspace", workspace, torch.uint8, nbytes), workspace.numel(),
                            _stream(stream)))
     return workspace
+
+
+STATIC_SCRATCH_BYTES = 64 << 20    # EASGD_STATIC_SCRATCH_BYTES of include/easgd.h
+
+
+def easgd_grad_static(dims: Sequence[int], W, X, y, G, loss=None, stream=None) -> None:
+    """easgd_grad on the library's own static workspace: nothing is allocated, here or in the library
+    (for callers that cannot allocate; shapes beyond STATIC_SCRATCH_BYTES of workspace are rejected)."""
+    arr, L = _dims(dims)
+    if W.dim() != 2 or X.dim() != 3 or y.dim() != 2:
+        raise ValueError("expected W[P][ld], X[P][b][d_in], y[P][b]")
+    P, ld = W.shape
+    b = X.shape[1]
+    N = easgd_mlp_num_params(dims)
+    if N == 0:
+        raise ValueError(f"invalid layer widths {list(dims)}")
+    if X.shape[0] != P or X.shape[2] != dims[0] or tuple(y.shape) != (P, b):
+        raise ValueError("X / y shapes do not match W and dims")
+    need = (P - 1) * ld + N
+    _check(_lib.easgd_grad_static(arr, L, _dev("W", W, torch.float32, need), ld,
+                                  _dev("X", X, torch.float32, P * b * dims[0]),
+                                  _dev("y", y, torch.int32, P * b), P, b,
+                                  _dev("G", G, torch.float32, need),
+                                  None if loss is None else _dev("loss", loss, torch.float32, P),
+                                  _stream(stream)))
 
 
 def easgd_mlp_round_workspace_bytes(dims: Sequence[int], P: int, b: int) -> int:

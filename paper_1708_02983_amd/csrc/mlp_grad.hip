@@ -23,6 +23,11 @@
 #include "gemm_mfma.h"
 #include <mutex>
 
+// The workspace of easgd_grad_static: device memory that belongs to the library, one copy per GPU, held from
+// the moment the library is loaded on that GPU until the process ends.  In host code this name is only a
+// stand-in for the symbol; the device address is looked up once per device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[EASGD_STATIC_SCRATCH_BYTES];
+
 namespace easgd {
 
 static constexpr int MAX_LAYERS = 8;
@@ -507,6 +512,32 @@ static SideLane *side_lane()       // call with side_mutex held; nullptr when no
     return ln.ok ? &ln : nullptr;
 }
 
+// Device address of `scratch` on the current device, looked up on the first call per device (with that device
+// current) and kept; nullptr (and the error string set) when the lookup fails.
+static void *static_scratch(const char *name)
+{
+    static std::mutex lookup_mutex;
+    static void *ptrs[MAX_DEVICES] = {nullptr};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        fail(EASGD_ELAUNCH, "%s: no current device", name);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> guard(lookup_mutex);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            fail(EASGD_ELAUNCH, "%s: address of the static workspace: %s", name, hipGetErrorString(e));
+            return nullptr;
+        }
+        ptrs[dev] = p;
+    }
+    return ptrs[dev];
+}
+
 }  // namespace easgd
 
 extern "C" {
@@ -537,6 +568,21 @@ int easgd_grad(const int *dims, int n_layers, const float *W, size_t ld, const f
 {
     return easgd::grad_impl("easgd_grad", dims, n_layers, W, ld, X, y, P, b, G, loss, workspace, workspace_bytes,
                             stream, nullptr);
+}
+
+int easgd_grad_static(const int *dims, int n_layers, const float *W, size_t ld, const float *X, const int32_t *y,
+                      int P, int b, float *G, float *loss, void *stream)
+{
+    easgd::GradPlan pl;
+    if (!easgd::make_plan(dims, n_layers, P, b, pl))
+        return easgd::fail(EASGD_EINVAL, "easgd_grad_static: need 1 <= n_layers <= %d, all dims >= 1, P >= 1, b >= 1", easgd::MAX_LAYERS);
+    if (pl.bytes > (size_t)EASGD_STATIC_SCRATCH_BYTES)
+        return easgd::fail(EASGD_EWORKSPACE, "easgd_grad_static: this shape needs %zu bytes of workspace, the static workspace holds %zu; "
+                           "use easgd_grad with a workspace of the caller", pl.bytes, (size_t)EASGD_STATIC_SCRATCH_BYTES);
+    void *ws = easgd::static_scratch("easgd_grad_static");
+    if (!ws) return EASGD_ELAUNCH;
+    return easgd::grad_impl("easgd_grad_static", dims, n_layers, W, ld, X, y, P, b, G, loss, ws,
+                            (size_t)EASGD_STATIC_SCRATCH_BYTES, stream, nullptr);
 }
 
 int easgd_grad_bf16(const int *dims, int n_layers, const float *W, size_t ld, const float *X, const int32_t *y,

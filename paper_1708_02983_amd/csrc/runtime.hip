@@ -43,7 +43,7 @@ extern "C" {
 
 const char *easgd_last_error(void) { return easgd::g_err; }
 
-int easgd_version(void) { return 330; }
+int easgd_version(void) { return 400; }
 
 int easgd_set_option(int option, long value)
 {

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
             "easgd_mlp_num_params", "easgd_last_error", "easgd_version", "easgd_set_option",
             "easgd_get_option", "easgd_stream_copy", "easgd_stream_triad", "easgd_mlp_round", "easgd_mlp_round_bf16v",
             "easgd_mlp_round_workspace_bytes", "easgd_sync_round_bf16", "measgd_round_bf16", "measgd_round_bf16v",
-            "easgd_grad_bf16", "sync_sgd_round"} <= set(names)
+            "easgd_grad_bf16", "easgd_grad_static", "sync_sgd_round"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/easgd.h but not exported"
 

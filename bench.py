@@ -11,10 +11,17 @@ rounds are also timed through the two-call path, `easgd_grad` followed by
 matrix-product kernels for the MFMA roofline.  For the update-only workloads
 cfg4/cfg5 a step is the elastic update alone.
 The default workload is cfg2 (MLP 784-1024-1024-10, P=16, b=128); the default
-run also measures the elastic update at AlexNet size (cfg4, cfg5; with fp32 and
-with bfloat16-stored gradients and momentum buffers, the latter an extension)
-and the synchronous SGD round, and reports those under "elastic_update" in the
-same JSON line.
+run also times the other two training workloads (cfg1, cfg3; "training_workloads"
+in the JSON line), measures the elastic update at AlexNet size (cfg4, cfg5; with
+fp32 and with bfloat16-stored gradients and momentum buffers, the latter an
+extension) and the synchronous SGD round ("elastic_update"), and times the CPU
+oracle on the host cores for every workload.
+
+Every GPU leg starts with an untimed pre-roll of the same calls (at least
+PREROLL_MIN_S, until two consecutive blocks of rounds agree within 2 %): the
+first milliseconds of a process run at start-up clocks and with cold code, and
+a timed region of a few milliseconds would otherwise measure those.  Then
+`warmup` untimed rounds, then exactly `steps` timed rounds.
 
 Prints ONE JSON line.  Kernel-phase durations are measured with HIP events on
 the stream the kernels are launched on.
@@ -72,6 +79,36 @@ def _sum_ms(starts, stops):
     return float(sum(a.elapsed_time(b) for a, b in zip(starts, stops)))
 
 
+PREROLL_MIN_S = 0.25
+PREROLL_MAX_S = 2.0
+
+
+def preroll(step, block, first=0):
+    """Untimed rounds ahead of a measurement: blocks of `block` calls of step(t) until at least PREROLL_MIN_S
+    have passed and two consecutive blocks take the same time within 2 % (or PREROLL_MAX_S have passed).
+    Returns (number of calls made, report)."""
+    import torch
+    t, prev, stable = first, None, False
+    torch.cuda.synchronize()
+    start = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        for _ in range(block):
+            step(t)
+            t += 1
+        torch.cuda.synchronize()
+        now = time.perf_counter()
+        dt = now - t0
+        if prev is not None and now - start >= PREROLL_MIN_S and abs(dt - prev) <= 0.02 * min(dt, prev):
+            stable = True
+            break
+        if now - start >= PREROLL_MAX_S:
+            break
+        prev = dt
+    return t - first, {"preroll_s": round(time.perf_counter() - start, 3), "preroll_rounds": t - first,
+                       "preroll_stable": stable}
+
+
 # ---------------------------------------------------------------------------
 # GPU legs
 # ---------------------------------------------------------------------------
@@ -121,25 +158,31 @@ def bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=False, g_bf16=F
         if ev:
             ev[2].record()
 
+    done, pre = preroll(step, max(steps, 20))
     for t in range(warmup):
-        step(t)
+        step(done + t)
     # the timed region: exactly `steps` rounds, nothing but the library calls between the two synchronisations
     torch.cuda.synchronize()
+    c0 = hip.launch_count()
     t0 = time.perf_counter()
     for t in range(steps):
-        step(warmup + t)
+        step(done + warmup + t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    # a second, instrumented pass over as many rounds gives the duration of each phase from HIP events
-    # (recording events costs some microseconds per round, so it stays out of the timed region)
-    e0, e1, e2 = _events(steps), _events(steps), _events(steps)
-    for t in range(steps):
-        step(warmup + steps + t, (e0[t], e1[t], e2[t]))
+    launches = (hip.launch_count() - c0) / steps
+    # a second, instrumented pass gives the duration of each phase from HIP events recorded on the launch stream
+    # (recording them costs some microseconds per round, so it stays out of the timed region); at least 50 rounds,
+    # so that the average does not hang on a handful of launches
+    n_ev = max(steps, 50)
+    e0, e1, e2 = _events(n_ev), _events(n_ev), _events(n_ev)
+    for t in range(n_ev):
+        step(done + warmup + steps + t, (e0[t], e1[t], e2[t]))
     torch.cuda.synchronize()
     assert bool(torch.isfinite(dWc).all()), "center weights diverged"
-    grad_ms = _sum_ms(e0, e1) / steps
-    upd_ms = _sum_ms(e1, e2) / steps
-    return {"elapsed_s": elapsed, "ms_per_step": 1e3 * elapsed / steps, "grad_ms": grad_ms, "update_ms": upd_ms}
+    grad_ms = _sum_ms(e0, e1) / n_ev
+    upd_ms = _sum_ms(e1, e2) / n_ev
+    return {"elapsed_s": elapsed, "ms_per_step": 1e3 * elapsed / steps, "grad_ms": grad_ms, "update_ms": upd_ms,
+            "launches_per_round": launches, "event_rounds": n_ev, **pre}
 
 
 def bench_host_fed(hip, wl, steps, warmup):
@@ -242,20 +285,21 @@ def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
         else:
             hip.easgd_sync_round(dW, Gs[t % pool], dWc, wl.eta, wl.rho)
 
+    done, pre = preroll(step, 20)
     for t in range(warmup):
-        step(t)
+        step(done + t)
     e0, e1 = _events(steps), _events(steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(steps):
         e0[t].record()
-        step(warmup + t)
+        step(done + warmup + t)
         e1[t].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     assert bool(torch.isfinite(dWc).all()) and bool(torch.isfinite(dW[0, :4096]).all())
     kernel_ms = _sum_ms(e0, e1) / steps
-    return {"elapsed_s": elapsed, "ms_per_step": 1e3 * elapsed / steps, "update_ms": kernel_ms}
+    return {"elapsed_s": elapsed, "ms_per_step": 1e3 * elapsed / steps, "update_ms": kernel_ms, **pre}
 
 
 def triad_ceiling(hip, n=488_000_000, reps=20):
@@ -275,37 +319,50 @@ def triad_ceiling(hip, n=488_000_000, reps=20):
     return 12.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
-# HBM bytes per launch of the elastic update measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
-# the reading of the same counter for the triad kernel of known traffic (x2.000 and x1.000); see
-# profiles/elastic_update_cfg4_cfg5_hbm_traffic.md.  Keyed by (momentum, P, N).
-MEASURED_TRAFFIC_BYTES = {
-    (False, 8, 61_000_000): 2_025_422.5 * 1024 * 2.000 + 2_144_537.9 * 1024 * 1.000,
-    (True, 16, 61_000_000): 5_838_007.1 * 1024 * 2.000 + 7_863_305.8 * 1024 * 1.000,
+
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled by the reading
+# of the same counter for the triad kernel of known traffic (x2.000 and x1.000).  They are counter readings of an
+# earlier profiling session, not of this run: each entry names the summary under profiles/ it comes from, and all of
+# them are dropped from the JSON line (traffic: null) when the running library reports another version than the one
+# that was profiled, or non-default launch options.
+TRAFFIC_PROFILES = {
+    ("elastic", False, 8, 61_000_000): (2_025_422.5 * 1024 * 2.000 + 2_144_537.9 * 1024 * 1.000,
+                                        "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
+    ("elastic", True, 16, 61_000_000): (5_838_007.1 * 1024 * 2.000 + 7_863_305.8 * 1024 * 1.000,
+                                        "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
+    ("elastic_bf16", False, 8, 61_000_000): (1_548_854.4 * 1024 * 2.000 + 2_144_545.8 * 1024 * 1.000,
+                                             "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
+    ("elastic_bf16", True, 16, 61_000_000): (3_931_683.7 * 1024 * 2.000 + 5_957_037.5 * 1024 * 1.000,
+                                             "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
+    ("grad", "cfg2"): (131_933.3 * 1024 * 2.000 + 149_345.8 * 1024 * 1.000, "profiles/easgd_grad_cfg2_hbm_traffic.md"),
 }
-# the same for the kernels with bfloat16-stored gradients (and momentum buffers)
-MEASURED_TRAFFIC_BYTES_BF16 = {
-    (False, 8, 61_000_000): 1_548_854.4 * 1024 * 2.000 + 2_144_545.8 * 1024 * 1.000,
-    (True, 16, 61_000_000): 3_931_683.7 * 1024 * 2.000 + 5_957_037.5 * 1024 * 1.000,
-}
+TRAFFIC_PROFILED_VERSION = 330      # easgd_version() of the library the summaries above were taken with
 
 
-# HBM bytes per easgd_grad launch (all its kernels), measured the same way; see profiles/easgd_grad_cfg2_hbm_traffic.md.
-# Keyed by workload name.
-MEASURED_GRAD_TRAFFIC_BYTES = {
-    "cfg2": 131_933.3 * 1024 * 2.000 + 149_345.8 * 1024 * 1.000,
-}
+def traffic_fields(hip, key):
+    """`traffic` (bytes per launch) and its provenance for a roofline object; None when the profile is stale."""
+    entry = TRAFFIC_PROFILES.get(key)
+    default_opts = (hip.get_option(hip.OPT_UPDATE_GROUPS) == 4 and hip.get_option(hip.OPT_UPDATE_NONTEMPORAL) == 1
+                    and hip.get_option(hip.OPT_UPDATE_BLOCKS_PER_CU) == 0 and hip.get_option(hip.OPT_GEMM_TILE) == 0)
+    if entry is None or not default_opts or hip.version() != TRAFFIC_PROFILED_VERSION:
+        return {"traffic": None}
+    return {"traffic": entry[0],
+            "traffic_from": {"profile": entry[1], "library_version": TRAFFIC_PROFILED_VERSION,
+                             "note": "counter reading of an earlier rocprofv3 session with this library version, "
+                                     "not of this run"}}
 
 
-def hbm_roofline(wl, update_ms, ceiling_gbs=None):
-    achieved = update_bytes(wl) / (update_ms * 1e-3) / 1e9
-    out = {"bound": "hbm", "kernel": "elastic_vec4_kernel (measgd)" if wl.momentum else "elastic_vec4_kernel (easgd)",
-           "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-           "frac": round(achieved / HBM_PEAK_GBS, 4),
-           "traffic": MEASURED_TRAFFIC_BYTES.get((wl.momentum, wl.P, wl.N)),
-           "algorithmic_bytes_per_launch": update_bytes(wl), "avg_launch_ms": round(update_ms, 4)}
-    if ceiling_gbs:
-        out["measured_triad_ceiling_GBs"] = round(ceiling_gbs, 1)
-        out["frac_of_triad_ceiling"] = round(achieved / ceiling_gbs, 4)
+def hbm_roofline(hip, kernel, traffic_key, nbytes, update_ms, ceilings):
+    """HBM roofline object of one streaming kernel: algorithmic bytes per launch / average launch duration."""
+    achieved = nbytes / (update_ms * 1e-3) / 1e9
+    out = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": round(achieved / HBM_PEAK_GBS, 4), **traffic_fields(hip, traffic_key),
+           "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": round(update_ms, 4),
+           "target_frac": 0.80, "meets_target": bool(achieved / HBM_PEAK_GBS >= 0.80)}
+    for name, gbs in (ceilings or {}).items():
+        out[f"measured_{name}_ceiling_GBs"] = round(gbs, 1)
+        out[f"frac_of_{name}_ceiling"] = round(achieved / gbs, 4)
     return out
 
 
@@ -314,6 +371,9 @@ def hbm_roofline(wl, update_ms, ceiling_gbs=None):
 # ---------------------------------------------------------------------------
 
 def cpu_baseline(wl, budget_s=12.0):
+    """The oracle as it stands on this host.  Training workloads: whole rounds for about budget_s seconds.
+    Update-only workloads: at least 3 rounds at FULL size (all P replicas x N parameters in host memory, inputs
+    drawn by several threads) on all host cores, then the plain single-thread loop on a 1/16 slice."""
     import oracle
     F = np.float32
     cores = oracle.num_threads()
@@ -337,15 +397,15 @@ def cpu_baseline(wl, budget_s=12.0):
         return {"value": round(done / el, 4), "unit": "rounds/s", "cores": cores, "kind": "oracle",
                 "sample": f"{done} whole rounds (numpy fp64 gradient of all {wl.P} workers + C elastic update) "
                           f"of the same workload in {el:.1f} s"}
-    # update-only: a 1/8 slice of the parameter index (the update is independent per parameter), first on all
-    # host cores, then on a single thread (the plain scalar loop)
-    frac = 8
-    n = wl.N // frac
-    W, Wc = workloads.update_state(wl.P, n)
-    G = workloads.update_gradients(wl.P, n, 0)
-    V = np.zeros_like(W)
+    t_gen = time.perf_counter()
+    threads = min(16, os.cpu_count() or 8)
+    W = workloads.host_normal_rows(wl.P, wl.N, workloads.WEIGHT_STD, 5, threads=threads)
+    G = workloads.host_normal_rows(wl.P, wl.N, workloads.GRADIENT_STD, 6, threads=threads)
+    Wc = workloads.host_normal_rows(1, wl.N, workloads.WEIGHT_STD, 7, threads=threads)[0]
+    V = np.zeros_like(W) if wl.momentum else None
+    t_gen = time.perf_counter() - t_gen
 
-    def timed(budget, cap):
+    def timed(W, V, G, Wc, budget, at_least, cap):
         done, t0 = 0, time.perf_counter()
         while True:
             if wl.momentum:
@@ -354,25 +414,116 @@ def cpu_baseline(wl, budget_s=12.0):
                 oracle.easgd_round(W, G, Wc, F(wl.eta), F(wl.rho))
             done += 1
             el = time.perf_counter() - t0
-            if el >= budget or done >= cap:
+            if done >= at_least and (el >= budget or done >= cap):
                 return done, el
 
-    done, el = timed(budget_s / 2, 400)
+    timed(W, V, G, Wc, 0.0, 1, 1)                  # first touch of every page by the threads that will use it
+    done, el = timed(W, V, G, Wc, budget_s, 3, 100)
+    frac = 16
+    n = wl.N // frac
+    sW, sG, sWc = np.ascontiguousarray(W[:, :n]), np.ascontiguousarray(G[:, :n]), Wc[:n].copy()
+    sV = np.zeros_like(sW) if wl.momentum else None
     oracle.set_num_threads(1)
     try:
-        done1, el1 = timed(budget_s / 4, 50)
+        done1, el1 = timed(sW, sV, sG, sWc, 2.0, 1, 20)
     finally:
         oracle.set_num_threads(0)
-    return {"value": round(done / el / frac, 4), "unit": "rounds/s", "cores": cores, "kind": "oracle",
-            "sample": f"{done} rounds on a 1/{frac} slice of the parameter index ({n} of {wl.N} parameters, all "
-                      f"{wl.P} replicas) in {el:.1f} s; rate divided by {frac}",
-            "GBs": round(update_bytes(wl) / frac * done / el / 1e9, 2),
+    return {"value": round(done / el, 4), "unit": "rounds/s", "cores": cores, "kind": "oracle",
+            "sample": f"{done} rounds at full size ({wl.P} replicas x {wl.N} parameters, "
+                      f"{update_bytes(wl) / 1e9:.2f} GB streamed per round) in {el:.1f} s after one untimed round; "
+                      f"inputs drawn in {t_gen:.1f} s",
+            "GBs": round(update_bytes(wl) * done / el / 1e9, 2),
             "single_thread": {"value": round(done1 / el1 / frac, 4), "unit": "rounds/s",
                               "GBs": round(update_bytes(wl) / frac * done1 / el1 / 1e9, 2),
-                              "sample": f"{done1} rounds on the same slice in {el1:.1f} s"}}
+                              "sample": f"{done1} rounds on a 1/{frac} slice of the parameter index in {el1:.1f} s, "
+                                        f"rate divided by {frac}"}}
 
 
 # ---------------------------------------------------------------------------
+
+def update_roofline(hip, wl, rule, update_ms, ceilings):
+    """HBM roofline of one streaming update launch at the workload's size."""
+    P, N = wl.P, wl.N
+    if rule == "sync_sgd":
+        return hbm_roofline(hip, "sync_sgd_vec4_kernel", ("sync_sgd", wl.momentum, P, N), 12 * P * N, update_ms, ceilings)
+    if rule == "elastic_bf16":
+        return hbm_roofline(hip, "elastic_bf16_vec4_kernel", ("elastic_bf16", wl.momentum, P, N),
+                            N * ((14 if wl.momentum else 10) * P + 8), update_ms, ceilings)
+    return hbm_roofline(hip, "elastic_vec4_kernel (measgd)" if wl.momentum else "elastic_vec4_kernel (easgd)",
+                        ("elastic", wl.momentum, P, N), update_bytes(wl), update_ms, ceilings)
+
+
+def mfma_roofline(hip, kernel, traffic_key, flops, ms):
+    tflops = flops / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": kernel, "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4), **traffic_fields(hip, traffic_key),
+            "useful_flops_per_launch": flops, "avg_launch_ms": round(ms, 4)}
+
+
+def training_report(hip, wl, steps, warmup, name, full):
+    """One training workload through the one-call path (the headline) and the two-call path; full=True adds the
+    bfloat16-storage extensions and the host-fed leg."""
+    r1 = bench_training(hip, wl, steps, warmup, one_call=True)
+    r = bench_training(hip, wl, steps, warmup, one_call=False)
+    out = {"value": round(steps / r1["elapsed_s"], 2), "ms_per_step": round(r1["ms_per_step"], 4),
+           "path": "easgd_mlp_round: one call per round, elastic update fused into backward propagation",
+           "round_call_ms": round(r1["grad_ms"], 4), "preroll_s": r1["preroll_s"],
+           "preroll_stable": r1["preroll_stable"], "launches_per_round": r1["launches_per_round"],
+           "two_call_path": {"rounds_per_s": round(steps / r["elapsed_s"], 2),
+                             "ms_per_step": round(r["ms_per_step"], 4),
+                             "launches_per_round": r["launches_per_round"],
+                             "phases_ms": {"easgd_grad": round(r["grad_ms"], 4),
+                                           "elastic_update": round(r["update_ms"], 4)}}}
+    # the dominant kernels are the matrix products.  `roofline`: all products of one easgd_grad call of the two-call
+    # path (matrix products, softmax and nothing else), useful flops over the call's duration from HIP events.
+    # `roofline_one_call`: the same useful flops over the duration of the whole easgd_mlp_round call, whose
+    # products also apply the elastic update in their epilogues -- the path `value` times.
+    out["roofline"] = mfma_roofline(hip, "gemm_mfma_kernel (all products of easgd_grad, two-call path)",
+                                    ("grad", name), grad_flops(wl), r["grad_ms"])
+    out["roofline_one_call"] = mfma_roofline(hip, "gemm_mfma_kernel + elastic epilogues (all launches of easgd_mlp_round)",
+                                             ("round", name), grad_flops(wl), r1["grad_ms"])
+    out["update_in_round"] = {"GBs_algorithmic": round(update_bytes(wl) / (r["update_ms"] * 1e-3) / 1e9, 1),
+                              "note": "elastic update of the two-call path; replicas of this size are served partly "
+                                      "from the 256 MB last-level cache, so this is not an HBM figure"}
+    if wl.momentum:
+        # an extension (the paper names low precision only as future work): the same rounds with the momentum
+        # buffers stored as bfloat16
+        b1 = bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=True)
+        out["bf16_momentum_storage"] = {
+            "rounds_per_s": round(steps / b1["elapsed_s"], 2), "ms_per_step": round(b1["ms_per_step"], 4),
+            "note": "extension: easgd_mlp_round_bf16v, bfloat16 momentum buffers; fp32 replicas, center, gradients "
+                    "and arithmetic"}
+        if full:
+            b2 = bench_training(hip, wl, steps, warmup, one_call=False, v_bf16=True)
+            out["bf16_momentum_storage"]["two_call_path"] = {
+                "rounds_per_s": round(steps / b2["elapsed_s"], 2), "ms_per_step": round(b2["ms_per_step"], 4),
+                "phases_ms": {"easgd_grad": round(b2["grad_ms"], 4), "elastic_update": round(b2["update_ms"], 4)}}
+    if full:
+        # an extension: the two-call path with the gradients (and momentum buffers) stored as bfloat16
+        g = bench_training(hip, wl, steps, warmup, one_call=False, v_bf16=wl.momentum, g_bf16=True)
+        out["two_call_path"]["with_bf16_gradient_storage"] = {
+            "rounds_per_s": round(steps / g["elapsed_s"], 2), "ms_per_step": round(g["ms_per_step"], 4),
+            "phases_ms": {"easgd_grad": round(g["grad_ms"], 4), "elastic_update": round(g["update_ms"], 4)},
+            "note": "extension: easgd_grad writes bfloat16 gradients, the update reads them"
+                    + (" and keeps bfloat16 momentum buffers" if wl.momentum else "")}
+        out["host_fed"] = bench_host_fed(hip, wl, steps, warmup)
+    return out
+
+
+def mix32_ceiling(hip, n=366_000_000, reps=20):
+    """Attainable HBM bandwidth (GB/s) for a 3-read/2-write stream, the mix of the momentum update."""
+    import torch
+    bufs = [torch.ones(n, dtype=torch.float32, device="cuda") for _ in range(5)]
+    for _ in range(3):
+        hip.stream_mix32(*bufs, 0.5)
+    e0, e1 = _events(1)[0], _events(1)[0]
+    e0.record()
+    for _ in range(reps):
+        hip.stream_mix32(*bufs, 0.5)
+    e1.record()
+    torch.cuda.synchronize()
+    return 20.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -415,101 +566,70 @@ def main():
     steps = args.steps if args.steps is not None else (300 if wl.has_grad else 100)
     warmup = args.warmup if args.warmup is not None else (20 if wl.has_grad else 5)
 
-    ceiling = triad_ceiling(hip)
+    ceilings = {"triad": triad_ceiling(hip)}
+    mix = getattr(hip, "stream_mix32", None)
+    if mix is not None:
+        ceilings["3r2w"] = mix32_ceiling(hip)
     line = {"metric": "Sync EASGD rounds/sec", "unit": "rounds/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
             "config": {"workload": DESCRIPTIONS[args.workload], "P": wl.P, "params_per_replica": wl.N,
-                       "eta": wl.eta, "rho": wl.rho, "delta": wl.delta}}
+                       "eta": wl.eta, "rho": wl.rho, "delta": wl.delta},
+            "library_version": hip.version()}
     if wl.has_grad:
-        r1 = bench_training(hip, wl, steps, warmup, one_call=True)
-        r = bench_training(hip, wl, steps, warmup, one_call=False)
-        tflops = grad_flops(wl) / (r["grad_ms"] * 1e-3) / 1e12
-        line.update({"value": round(steps / r1["elapsed_s"], 2), "ms_per_step": round(r1["ms_per_step"], 4),
-                     "path": "easgd_mlp_round: one call per round, elastic update fused into backward propagation",
-                     "round_call_ms": round(r1["grad_ms"], 4),
-                     "two_call_path": {"rounds_per_s": round(steps / r["elapsed_s"], 2),
-                                       "ms_per_step": round(r["ms_per_step"], 4),
-                                       "phases_ms": {"easgd_grad": round(r["grad_ms"], 4),
-                                                     "elastic_update": round(r["update_ms"], 4)}}})
-        # an extension: the two-call path with the gradients (and momentum buffers) stored as bfloat16
-        g = bench_training(hip, wl, steps, warmup, one_call=False, v_bf16=wl.momentum, g_bf16=True)
-        line["two_call_path"]["with_bf16_gradient_storage"] = {
-            "rounds_per_s": round(steps / g["elapsed_s"], 2), "ms_per_step": round(g["ms_per_step"], 4),
-            "phases_ms": {"easgd_grad": round(g["grad_ms"], 4), "elastic_update": round(g["update_ms"], 4)},
-            "note": "extension: easgd_grad writes bfloat16 gradients, the update reads them"
-                    + (" and keeps bfloat16 momentum buffers" if wl.momentum else "")}
-        line["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all products of easgd_grad, two-call path)",
-                            "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                            "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4),
-                            "traffic": MEASURED_GRAD_TRAFFIC_BYTES.get(args.workload),
-                            "useful_flops_per_launch": grad_flops(wl), "avg_launch_ms": round(r["grad_ms"], 4)}
-        if wl.momentum:
-            # an extension (the paper names low precision only as future work): the same rounds with the momentum
-            # buffers stored as bfloat16
-            b1 = bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=True)
-            b2 = bench_training(hip, wl, steps, warmup, one_call=False, v_bf16=True)
-            line["bf16_momentum_storage"] = {
-                "rounds_per_s": round(steps / b1["elapsed_s"], 2), "ms_per_step": round(b1["ms_per_step"], 4),
-                "two_call_path": {"rounds_per_s": round(steps / b2["elapsed_s"], 2),
-                                  "ms_per_step": round(b2["ms_per_step"], 4),
-                                  "phases_ms": {"easgd_grad": round(b2["grad_ms"], 4),
-                                                "elastic_update": round(b2["update_ms"], 4)}},
-                "note": "extension: easgd_mlp_round / measgd_round_bf16v with bfloat16 momentum buffers; "
-                        "fp32 replicas, center, gradients and arithmetic"}
-        line["host_fed"] = bench_host_fed(hip, wl, steps, warmup)
-        line["update_in_round"] = {"GBs_algorithmic": round(update_bytes(wl) / (r["update_ms"] * 1e-3) / 1e9, 1),
-                                   "note": "replicas of this workload fit the 256 MB last-level cache only partly; "
-                                           "not an HBM figure"}
+        line.update(training_report(hip, wl, steps, warmup, args.workload, full=True))
     else:
         r = bench_update_only(hip, wl, steps, warmup)
-        line.update({"value": round(steps / r["elapsed_s"], 2), "ms_per_step": round(r["ms_per_step"], 4)})
-        line["roofline"] = hbm_roofline(wl, r["update_ms"], ceiling)
+        line.update({"value": round(steps / r["elapsed_s"], 2), "ms_per_step": round(r["ms_per_step"], 4),
+                     "preroll_s": r["preroll_s"]})
+        line["roofline"] = update_roofline(hip, wl, "elastic", r["update_ms"], ceilings)
 
     if wl.has_grad and not args.no_extras:
+        # the other two training workloads, at the same step counts (cfg3 is the one that exercises the momentum
+        # rule Eq. (5),(6) and is large enough to matter for both rooflines; cfg1 is bound by launch latency)
+        others = {}
+        for name in ("cfg1", "cfg3"):
+            if name != args.workload:
+                others[name] = training_report(hip, workloads.WORKLOADS[name], steps, warmup, name, full=False)
+                others[name]["workload"] = DESCRIPTIONS[name]
+                torch.cuda.empty_cache()
+        line["training_workloads"] = others
         extra = {}
         for name in ("cfg4", "cfg5"):
             w2 = workloads.WORKLOADS[name]
             r2 = bench_update_only(hip, w2, 100, 5)
             extra[name] = {"workload": DESCRIPTIONS[name], "rounds_per_s": round(100 / r2["elapsed_s"], 2),
-                           "ms_per_step": round(r2["ms_per_step"], 4), "roofline": hbm_roofline(w2, r2["update_ms"], ceiling)}
+                           "ms_per_step": round(r2["ms_per_step"], 4), "preroll_s": r2["preroll_s"],
+                           "roofline": update_roofline(hip, w2, "elastic", r2["update_ms"], ceilings)}
             torch.cuda.empty_cache()
         # the method's point of comparison on the same replicas: synchronous data-parallel SGD (gradient sum
         # applied to every copy); per parameter and worker it reads g and W and writes W
         w4 = workloads.WORKLOADS["cfg4"]
         r3 = bench_update_only(hip, w4, 100, 5, rule="sync_sgd")
-        sgd_bytes = 12 * w4.P * w4.N
-        gbs = sgd_bytes / (r3["update_ms"] * 1e-3) / 1e9
         extra["sync_sgd_cfg4_shape"] = {
             "workload": "synchronous data-parallel SGD round, P=8 replicas x 61M fp32 parameters (sync_sgd_round)",
             "rounds_per_s": round(100 / r3["elapsed_s"], 2), "ms_per_step": round(r3["ms_per_step"], 4),
-            "roofline": {"bound": "hbm", "kernel": "sync_sgd_vec4_kernel", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                         "algorithmic_bytes_per_launch": sgd_bytes, "avg_launch_ms": round(r3["update_ms"], 4),
-                         "frac_of_triad_ceiling": round(gbs / ceiling, 4)}}
+            "roofline": update_roofline(hip, w4, "sync_sgd", r3["update_ms"], ceilings)}
         torch.cuda.empty_cache()
         # an extension (the paper names low precision only as future work): the same updates with gradients and
         # momentum buffers stored as bfloat16, fp32 replicas, center and arithmetic
         for name in ("cfg4", "cfg5"):
             w5 = workloads.WORKLOADS[name]
             r5 = bench_update_only(hip, w5, 100, 5, rule="elastic_bf16")
-            lp_bytes = w5.N * ((14 if w5.momentum else 10) * w5.P + 8)
-            gbs = lp_bytes / (r5["update_ms"] * 1e-3) / 1e9
             extra[name + "_bf16_storage"] = {
                 "workload": DESCRIPTIONS[name] + "; gradients" + (" and momentum buffers" if w5.momentum else "")
                             + " stored as bfloat16 (extension)",
                 "rounds_per_s": round(100 / r5["elapsed_s"], 2), "ms_per_step": round(r5["ms_per_step"], 4),
-                "roofline": {"bound": "hbm", "kernel": "elastic_bf16_vec4_kernel", "achieved": round(gbs, 1),
-                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-                             "traffic": MEASURED_TRAFFIC_BYTES_BF16.get((w5.momentum, w5.P, w5.N)),
-                             "algorithmic_bytes_per_launch": lp_bytes, "avg_launch_ms": round(r5["update_ms"], 4),
-                             "frac_of_triad_ceiling": round(gbs / ceiling, 4)}}
+                "roofline": update_roofline(hip, w5, "elastic_bf16", r5["update_ms"], ceilings)}
             torch.cuda.empty_cache()
         line["elastic_update"] = extra
 
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(wl)
+        line["cpu_baseline"] = cpu_baseline(wl, budget_s=8.0 if wl.has_grad else 4.0)
         if "elastic_update" in line:
-            line["elastic_update"]["cfg4"]["cpu_baseline"] = cpu_baseline(workloads.WORKLOADS["cfg4"], budget_s=8.0)
+            for name in ("cfg4", "cfg5"):
+                line["elastic_update"][name]["cpu_baseline"] = cpu_baseline(workloads.WORKLOADS[name], budget_s=2.0)
+        for name, sub in line.get("training_workloads", {}).items():
+            sub["cpu_baseline"] = cpu_baseline(workloads.WORKLOADS[name], budget_s=1.0 if name == "cfg1" else 6.0)
     print(json.dumps(line), flush=True)
 
 

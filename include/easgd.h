@@ -15,12 +15,21 @@
  *
  * Conventions shared by every entry point
  *   - every pointer marked DEVICE is a device (HBM) pointer owned by the caller;
- *     the library never allocates, frees or keeps a pointer after the call returns;
+ *     the library never allocates or frees device memory and never keeps a caller's
+ *     pointer after the call returns;
  *   - calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream); no host synchronisation happens inside;
- *   - the return value is an easgd_status; on error nothing was launched and
- *     easgd_last_error() describes the reason (thread-local string);
+ *   - the return value is an easgd_status and easgd_last_error() describes the reason
+ *     (thread-local string).  EASGD_EINVAL, EASGD_EWORKSPACE and EASGD_ERANGE are found
+ *     before anything is launched: the buffers are untouched.  EASGD_ELAUNCH is what the
+ *     HIP runtime reports when a launch, an event or a stream wait fails; the calls that
+ *     issue several kernels (easgd_grad*, easgd_mlp_round*) check once at their end, so
+ *     earlier kernels of the call may already be queued and the outputs are then undefined;
+ *   - fp32 pointers must be 4-byte aligned and bfloat16 pointers 2-byte aligned
+ *     (EASGD_EINVAL otherwise); stricter alignment selects the fast paths, see each call;
  *   - buffers of one call must not overlap each other;
+ *   - process-wide state: the launch-shape options below, a launch counter, and per device
+ *     what easgd_mlp_round and easgd_grad_static create on first use (described there);
  *   - all floating point is IEEE fp32 (storage and arithmetic), except the *_bf16 / *_bf16v entry points,
  *     which keep fp32 arithmetic and store gradients and momentum buffers as bfloat16;
  *   - replica matrices are [P][ld] row-major: row i is worker i, its first N
@@ -237,6 +246,14 @@ int easgd_grad_bf16(const int *dims, int n_layers,
  *   exchange is launched and Wc is not written.  A caller who wants workers to
  *   exchange only every tau-th round (a communication period; an extension, the
  *   paper's Sync EASGD exchanges in every round) passes rho = 0 in the rounds between.
+ *
+ * Library state: when the center rule is placed on a second stream (EASGD_OPT_ROUND_OVERLAP 2, or 1
+ * with P*N >= 2^24 and a first forward launch that fills the chip) the first such call on a device
+ * creates one non-blocking stream of default priority and two events for that device, which live
+ * until the process ends, and calls from several host threads are serialised on a mutex around
+ * their record/wait pair.  A caller that wants to capture the call in a HIP graph makes one eager
+ * call with the same shape first, so that the stream is not created under capture (or sets
+ * EASGD_OPT_ROUND_OVERLAP to 0 or 3, which keep the call on the caller's stream).
  * Errors: as easgd_grad.
  */
 size_t easgd_mlp_round_workspace_bytes(const int *dims, int n_layers, int P, int b);
@@ -261,11 +278,36 @@ int easgd_mlp_round_bf16v(const int *dims, int n_layers,
                           float eta, float rho, float delta,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * One matrix product of forward / backward propagation (Section 2.2) alone, for all P workers, through the
+ * tile selection and the MFMA kernels that easgd_grad uses for it (a testing aid: integer-valued operands
+ * make every product and partial sum exact in fp32, so the result can be checked bit for bit).
+ * For one layer with d_in inputs and d_out outputs, [W ; b] its packed (d_in+1) x d_out block:
+ *
+ *   kind 0  forward           out[w] = [A[w] 1] [W[w] ; b[w]]          b x d_out   (max(., 0) when relu != 0)
+ *   kind 1  weight gradient   out[w] = [A[w] 1]^T dZ[w]                (d_in+1) x d_out, i.e. [dW ; db]
+ *   kind 2  input gradient    out[w] = (dZ[w] W[w]^T) where A[w] > 0, else 0      b x d_in
+ *
+ *   A    DEVICE in  [P][b][d_in]     layer input (kind 2: only its sign is used)
+ *   Wl   DEVICE in  worker w's block at Wl + w*ld (kinds 0, 2; ignored for kind 1)
+ *   dZ   DEVICE in  [P][b][d_out]    (kinds 1, 2; ignored for kind 0)
+ *   out  DEVICE out worker w's result at out + w*out_ws, row-major with the widths above
+ * A, dZ, out 16-byte aligned.  Errors: EASGD_EINVAL, EASGD_ERANGE, EASGD_ELAUNCH.
+ */
+int easgd_layer_product(int kind, int d_in, int d_out, int P, int b,
+                        const float *A, const float *Wl, size_t ld, const float *dZ,
+                        float *out, size_t out_ws, int relu, void *stream);
+
 /* Number of parameters N of the packed layout for `dims`; 0 on invalid input. */
 size_t easgd_mlp_num_params(const int *dims, int n_layers);
 
 /*
- * Launch-shape knobs (performance only; results never depend on them).
+ * Launch-shape knobs (performance only).  Process-wide; each is one atomic word, so setting one from
+ * a host thread while another thread is inside a call is safe, and that call may use the old or the
+ * new value.  The results of the update entry points never depend on them (the worker sum has one
+ * fixed order).  EASGD_OPT_GEMM_TILE changes the slab depth of the matrix products and with it the
+ * order of their k sums: gradients then agree to rounding (about 1e-6 normwise), not bit for bit;
+ * the other matrix-product options change block order and launch grouping only (same bits).
  * Returns EASGD_EINVAL for an unknown option or an out-of-range value.
  */
 typedef enum {
@@ -304,6 +346,13 @@ long easgd_get_option(int option);
  */
 int easgd_stream_copy(float *dst, const float *src, size_t n, void *stream);
 int easgd_stream_triad(float *a, const float *b, const float *c, size_t n, float s, void *stream);
+/*   easgd_stream_mix32  a[j] = c[j] + s*d[j], b[j] = d[j] + s*e[j]   reads 12n bytes, writes 8n bytes
+ *                       (three reads and two writes per element: the mix of the momentum update) */
+int easgd_stream_mix32(float *a, float *b, const float *c, const float *d, const float *e, size_t n, float s, void *stream);
+
+/* Measurement aid: number of kernel launches the library has issued in this process so far
+ * (the difference across a call is the number of launches of that call). */
+unsigned long long easgd_launch_count(void);
 
 /* Message for the last error returned on the calling thread ("" if none). */
 const char *easgd_last_error(void);

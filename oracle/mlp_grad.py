@@ -33,7 +33,7 @@ def layer_slices(dims: Sequence[int]) -> List[Tuple[slice, slice]]:
 
 def mlp_grad(dims: Sequence[int], w_packed: np.ndarray, X: np.ndarray, y: np.ndarray,
              gate_flips: Iterable[Tuple[int, int, int]] = (), near_zero: Optional[list] = None,
-             near_zero_rel: float = 0.0):
+             near_zero_rel: float = 0.0, near_zero_ratio: Optional[list] = None):
     """Gradient (packed, fp32) and mean loss (float) for ONE worker.
 
     w_packed: [>=N] fp32, X: [b][dims[0]] fp32, y: [b] integer labels in [0, dims[-1]).
@@ -43,7 +43,8 @@ def mlp_grad(dims: Sequence[int], w_packed: np.ndarray, X: np.ndarray, y: np.nda
     differently, and either decision is a valid gradient of the fp32 computation.
     By default the gate is decided here in double.  For such ties a caller can
     ask which units are near zero (``near_zero`` list is filled with
-    (layer, sample, unit) where |z| <= near_zero_rel * max|Z_layer|) and evaluate
+    (layer, sample, unit) where |z| <= near_zero_rel * max|Z_layer|; ``near_zero_ratio``,
+    if given, receives |z| / max|Z_layer| of each of them) and evaluate
     the other decision by passing those triples in ``gate_flips``."""
     sl = layer_slices(dims)
     L = len(sl)
@@ -68,8 +69,11 @@ def mlp_grad(dims: Sequence[int], w_packed: np.ndarray, X: np.ndarray, y: np.nda
     flips = list(gate_flips)
     if near_zero is not None:
         for l in range(L - 1):
-            n_idx, u_idx = np.nonzero(np.abs(zs[l]) <= near_zero_rel * np.abs(zs[l]).max())
+            zmax = np.abs(zs[l]).max()
+            n_idx, u_idx = np.nonzero(np.abs(zs[l]) <= near_zero_rel * zmax)
             near_zero.extend((l, int(n), int(u)) for n, u in zip(n_idx, u_idx))
+            if near_zero_ratio is not None:
+                near_zero_ratio.extend(float(abs(zs[l][n, u]) / zmax) if zmax > 0 else 0.0 for n, u in zip(n_idx, u_idx))
 
     # backward propagation
     dz = np.exp(log_p)

@@ -68,12 +68,18 @@ def _load() -> ctypes.CDLL:
     lib.easgd_mlp_round.restype = i
     lib.easgd_mlp_round_bf16v.argtypes = [ip, i, vp, vp, vp, sz, vp, vp, i, i, vp, vp, f, f, f, vp, sz, vp]
     lib.easgd_mlp_round_bf16v.restype = i
+    lib.easgd_layer_product.argtypes = [i, i, i, i, i, vp, vp, sz, vp, vp, sz, i, vp]
+    lib.easgd_layer_product.restype = i
     lib.easgd_mlp_num_params.argtypes = [ip, i]
     lib.easgd_mlp_num_params.restype = sz
     lib.easgd_stream_copy.argtypes = [vp, vp, sz, vp]
     lib.easgd_stream_copy.restype = i
     lib.easgd_stream_triad.argtypes = [vp, vp, vp, sz, f, vp]
     lib.easgd_stream_triad.restype = i
+    lib.easgd_stream_mix32.argtypes = [vp, vp, vp, vp, vp, sz, f, vp]
+    lib.easgd_stream_mix32.restype = i
+    lib.easgd_launch_count.argtypes = []
+    lib.easgd_launch_count.restype = ctypes.c_ulonglong
     lib.easgd_set_option.argtypes = [i, ctypes.c_long]
     lib.easgd_set_option.restype = i
     lib.easgd_get_option.argtypes = [i]
@@ -221,6 +227,18 @@ def easgd_grad(dims: Sequence[int], W, X, y, G, loss=None, workspace=None, strea
     return workspace
 
 
+def easgd_layer_product(kind: int, d_in: int, d_out: int, A, out, Wl=None, dZ=None, ld: int = 0, out_ws: int = 0,
+                        relu: bool = False, stream=None) -> None:
+    """One product of forward / backward propagation alone (a testing aid): kind 0 forward, 1 weight gradient,
+    2 input gradient; A[P][b][d_in], Wl[P][ld], dZ[P][b][d_out], out[P][out_ws]."""
+    P, b = A.shape[0], A.shape[1]
+    _check(_lib.easgd_layer_product(kind, d_in, d_out, P, b, _dev("A", A, torch.float32, P * b * d_in),
+                                    None if Wl is None else _dev("Wl", Wl, torch.float32, (P - 1) * ld + (d_in + 1) * d_out),
+                                    ld, None if dZ is None else _dev("dZ", dZ, torch.float32, P * b * d_out),
+                                    _dev("out", out, torch.float32, (P - 1) * out_ws + 1), out_ws, int(relu),
+                                    _stream(stream)))
+
+
 STATIC_SCRATCH_BYTES = 64 << 20    # EASGD_STATIC_SCRATCH_BYTES of include/easgd.h
 
 
@@ -298,6 +316,19 @@ def stream_triad(a, b, c, s: float, stream=None) -> None:
     n = a.numel()
     _check(_lib.easgd_stream_triad(_dev("a", a, torch.float32, n), _dev("b", b, torch.float32, n),
                                    _dev("c", c, torch.float32, n), n, s, _stream(stream)))
+
+
+def stream_mix32(a, b, c, d, e, s: float, stream=None) -> None:
+    """Measurement aid: a[:] = c + s*d, b[:] = d + s*e (three reads, two writes per element)."""
+    n = a.numel()
+    _check(_lib.easgd_stream_mix32(_dev("a", a, torch.float32, n), _dev("b", b, torch.float32, n),
+                                   _dev("c", c, torch.float32, n), _dev("d", d, torch.float32, n),
+                                   _dev("e", e, torch.float32, n), n, s, _stream(stream)))
+
+
+def launch_count() -> int:
+    """Measurement aid: kernel launches issued by the library in this process so far."""
+    return int(_lib.easgd_launch_count())
 
 
 def set_option(option: int, value: int) -> None:

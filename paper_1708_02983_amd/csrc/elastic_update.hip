@@ -190,9 +190,9 @@ static void launch_vec4(int groups, dim3 grid, hipStream_t s, float *W, float *V
                         int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
 {
     switch (groups) {
-    case 1: hipLaunchKernelGGL((elastic_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    case 2: hipLaunchKernelGGL((elastic_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    default: hipLaunchKernelGGL((elastic_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 1: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 2: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    default: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
     }
 }
 
@@ -205,6 +205,8 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
     if (P < 1) return fail(EASGD_EINVAL, "%s: P must be >= 1, got %d", name, P);
     if (N == 0) return fail(EASGD_EINVAL, "%s: N must be >= 1", name);
     if (ld < N) return fail(EASGD_EINVAL, "%s: ld (%zu) < N (%zu)", name, ld, N);
+    if (!aligned_to(W, 4) || !aligned_to(G, 4) || !aligned_to(Wc, 4) || !aligned_to(V, 4))
+        return fail(EASGD_EINVAL, "%s: fp32 pointers must be 4-byte aligned", name);
     clear_error();
 
     const Options &opt = options();
@@ -227,12 +229,12 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
     const bool split = vec && P >= 4 && (N / 4 + 255) / 256 < (size_t)(2 * num_cus());
     if (split) {
         const dim3 split_grid((unsigned)((N / 4 + 63) / 64 > 0 ? (N / 4 + 63) / 64 : 1));
-        hipLaunchKernelGGL((elastic_split_kernel<MOM>), split_grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        EASGD_LAUNCH((elastic_split_kernel<MOM>), split_grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     } else if (vec) {
         if (opt.update_nontemporal) launch_vec4<MOM, true>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
         else launch_vec4<MOM, false>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     } else {
-        hipLaunchKernelGGL((elastic_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        EASGD_LAUNCH((elastic_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     }
     return check_launch(name);
 }
@@ -252,8 +254,8 @@ int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t 
     const size_t units = vec ? N / 4 : N;
     const size_t blocks = units / 256 + 1;    // the last block also owns the scalar tail
     if (blocks > 0x7fffffffu) return fail(EASGD_ERANGE, "center rule: N too large");
-    if (vec) hipLaunchKernelGGL((center_rule_kernel<f32x4>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
-    else hipLaunchKernelGGL((center_rule_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
+    if (vec) EASGD_LAUNCH((center_rule_kernel<f32x4>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
+    else EASGD_LAUNCH((center_rule_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
     return check_launch("center rule");
 }
 
@@ -360,9 +362,9 @@ template <bool MOM, bool NT>
 static void launch_sync_sgd(int groups, dim3 grid, hipStream_t s, float *W, float *V, const float *G, int P, size_t N,
                             size_t ld, float eta, float mu)
 {
-    if (groups == 4) hipLaunchKernelGGL((sync_sgd_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
-    else if (groups == 2) hipLaunchKernelGGL((sync_sgd_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
-    else hipLaunchKernelGGL((sync_sgd_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    if (groups == 4) EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else if (groups == 2) EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
 }
 
 template <bool MOM>
@@ -373,6 +375,8 @@ static int sync_sgd(float *W, float *V, const float *G, int P, size_t N, size_t 
     if (P < 1) return fail(EASGD_EINVAL, "%s: P must be >= 1, got %d", name, P);
     if (N == 0) return fail(EASGD_EINVAL, "%s: N must be >= 1", name);
     if (ld < N) return fail(EASGD_EINVAL, "%s: ld (%zu) < N (%zu)", name, ld, N);
+    if (!aligned_to(W, 4) || !aligned_to(G, 4) || !aligned_to(V, 4))
+        return fail(EASGD_EINVAL, "%s: fp32 pointers must be 4-byte aligned", name);
     clear_error();
     const Options &opt = options();
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -383,7 +387,7 @@ static int sync_sgd(float *W, float *V, const float *G, int P, size_t N, size_t 
     if (blocks == 0) blocks = 1;
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
     const dim3 grid((unsigned)blocks);
-    if (!vec) hipLaunchKernelGGL((sync_sgd_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    if (!vec) EASGD_LAUNCH((sync_sgd_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
     else if (opt.update_nontemporal) launch_sync_sgd<MOM, true>((int)groups, grid, s, W, V, G, P, N, ld, eta, mu);
     else launch_sync_sgd<MOM, false>((int)groups, grid, s, W, V, G, P, N, ld, eta, mu);
     return check_launch(name);

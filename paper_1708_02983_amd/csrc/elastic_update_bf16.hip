@@ -145,9 +145,9 @@ static void launch_bf16(int groups, dim3 grid, hipStream_t s, float *W, unsigned
                         float *Wc, int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
 {
     switch (groups) {
-    case 1: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 1, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    case 2: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 2, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    default: hipLaunchKernelGGL((elastic_bf16_vec4_kernel<MOM, NT, 4, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 1: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 1, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 2: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 2, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    default: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 4, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
     }
 }
 
@@ -161,6 +161,8 @@ static int elastic_round_bf16(const char *name, float *W, unsigned short *V, con
     if (P < 1) return fail(EASGD_EINVAL, "%s: P must be >= 1, got %d", name, P);
     if (N == 0) return fail(EASGD_EINVAL, "%s: N must be >= 1", name);
     if (ld < N) return fail(EASGD_EINVAL, "%s: ld (%zu) < N (%zu)", name, ld, N);
+    if (!aligned_to(W, 4) || !aligned_to(Wc, 4) || !aligned_to(G, sizeof(GT)) || !aligned_to(V, 2))
+        return fail(EASGD_EINVAL, "%s: fp32 pointers must be 4-byte aligned, bfloat16 pointers 2-byte aligned", name);
     clear_error();
 
     const Options &opt = options();
@@ -180,7 +182,7 @@ static int elastic_round_bf16(const char *name, float *W, unsigned short *V, con
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
     const dim3 grid((unsigned)blocks);
     if (!vec)
-        hipLaunchKernelGGL((elastic_bf16_scalar_kernel<MOM, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        EASGD_LAUNCH((elastic_bf16_scalar_kernel<MOM, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     else if (opt.update_nontemporal)
         launch_bf16<MOM, true, GT>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     else

@@ -347,8 +347,8 @@ static bool head_fits(const int *dims, int L) { return dims[L] <= HEAD_MAX_C; }
 template <int CP>
 static void launch_head_cp(const HeadArgs &h, unsigned blocks, hipStream_t s)
 {
-    if (h.d_in <= 1024) hipLaunchKernelGGL((mlp_head_kernel<HEAD_ROWS, CP, true>), dim3(blocks), dim3(256), 0, s, h);
-    else hipLaunchKernelGGL((mlp_head_kernel<HEAD_ROWS, CP, false>), dim3(blocks), dim3(256), 0, s, h);
+    if (h.d_in <= 1024) EASGD_LAUNCH((mlp_head_kernel<HEAD_ROWS, CP, true>), dim3(blocks), dim3(256), 0, s, h);
+    else EASGD_LAUNCH((mlp_head_kernel<HEAD_ROWS, CP, false>), dim3(blocks), dim3(256), 0, s, h);
 }
 
 static unsigned head_blocks(int P, int b) { return (unsigned)P * (unsigned)((b + HEAD_ROWS - 1) / HEAD_ROWS); }
@@ -405,7 +405,7 @@ template <int EPI, bool VEC_DW>
 static void launch_pair_da_narrow_dw(GemmArgs da, GemmArgs dw, hipStream_t s)
 {
     const unsigned n0 = place_blocks<64, 64>(da), n1 = place_blocks<128, 32>(dw);
-    hipLaunchKernelGGL((gemm_pair_kernel<64, 64, 32, 2, 2, K_CONTIG, K_CONTIG, true, EPI_MASK,
+    EASGD_LAUNCH((gemm_pair_kernel<64, 64, 32, 2, 2, K_CONTIG, K_CONTIG, true, EPI_MASK,
                                          128, 32, SPLIT_BK, 4, 1, MN_CONTIG, MN_CONTIG, VEC_DW, EPI>),
                        dim3(n0 + n1), dim3(256), 0, s, da, dw, n0);
 }
@@ -414,7 +414,7 @@ template <int EPI>
 static void launch_pair_dw_dw(GemmArgs d0, GemmArgs d1, hipStream_t s)
 {
     const unsigned n0 = place_blocks<64, 64>(d0), n1 = place_blocks<64, 64>(d1);
-    hipLaunchKernelGGL((gemm_pair_kernel<64, 64, 32, 2, 2, MN_CONTIG, MN_CONTIG, true, EPI,
+    EASGD_LAUNCH((gemm_pair_kernel<64, 64, 32, 2, 2, MN_CONTIG, MN_CONTIG, true, EPI,
                                          64, 64, 32, 2, 2, MN_CONTIG, MN_CONTIG, true, EPI>),
                        dim3(n0 + n1), dim3(256), 0, s, d0, d1, n0);
 }
@@ -430,8 +430,8 @@ static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
         total += a.ctr.blocks;
     }
     const dim3 grid((unsigned)total), block(WM * WN * 64);
-    if (vec) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, true, EPI>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI>), grid, block, 0, s, a);
+    if (vec) EASGD_LAUNCH((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, true, EPI>), grid, block, 0, s, a);
+    else EASGD_LAUNCH((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI>), grid, block, 0, s, a);
 }
 
 // Picks the tile shape.  Outputs at most 32 wide use a 128x32 tile.  Otherwise 64x64 blocks (four per
@@ -732,10 +732,10 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         if (L == 1) h.ctr = center_job;
         launch_head(h, s);
     } else {
-        hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) % 3], row_loss,
+        EASGD_LAUNCH(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, y, dz[(L - 1) % 3], row_loss,
                            rows, b, dims[L], pl.splits, (size_t)rows * dims[L]);
     }
-    if (loss) hipLaunchKernelGGL(mean_loss_kernel, dim3(P), dim3(64), 0, s, row_loss, loss, b);
+    if (loss) EASGD_LAUNCH(mean_loss_kernel, dim3(P), dim3(64), 0, s, row_loss, loss, b);
 
     // ---- backward propagation ----
     // The weight-gradient product of a layer is held back until the next product is known, because two
@@ -832,3 +832,51 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
 }
 
 }  // namespace easgd
+
+// One product of forward / backward propagation alone, through the same tile selection and kernels as the gradient.
+extern "C" int easgd_layer_product(int kind, int d_in, int d_out, int P, int b, const float *A, const float *Wl, size_t ld,
+                                   const float *dZ, float *out, size_t out_ws, int relu, void *stream)
+{
+    using namespace easgd;
+    const char *name = "easgd_layer_product";
+    if (kind < 0 || kind > 2 || d_in < 1 || d_out < 1 || P < 1 || b < 1) return fail(EASGD_EINVAL, "%s: bad kind or size", name);
+    if (!A || !out || (kind != 1 && !Wl) || (kind != 0 && !dZ)) return fail(EASGD_EINVAL, "%s: NULL pointer", name);
+    if (!aligned16(A) || !aligned16(out) || !aligned16(dZ) || !aligned_to(Wl, 4))
+        return fail(EASGD_EINVAL, "%s: A, dZ, out must be 16-byte aligned, Wl 4-byte aligned", name);
+    const size_t out_need = kind == 0 ? (size_t)b * d_out : kind == 1 ? (size_t)(d_in + 1) * d_out : (size_t)b * d_in;
+    if (out_ws < out_need) return fail(EASGD_EINVAL, "%s: out_ws (%zu) below one worker's result (%zu)", name, out_ws, out_need);
+    if (kind != 1 && ld < (size_t)(d_in + 1) * d_out) return fail(EASGD_EINVAL, "%s: ld below one layer block", name);
+    if ((size_t)(d_in + 1) * d_out > 0x3fffffffull || (size_t)b * d_in > 0x3fffffffull || (size_t)b * d_out > 0x3fffffffull ||
+        (size_t)P * b > 0x7fffffffull)
+        return fail(EASGD_ERANGE, "%s: an operand exceeds 2^30-1 elements per worker", name);
+    clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmArgs a = {};
+    a.P = P; a.splits = 1;
+    if (kind == 0) {            // Z = [A 1] [W ; b]
+        a.A = A; a.a_ws = (size_t)b * d_in; a.lda = d_in; a.a_lim = d_in; a.a_ones = d_in;
+        a.B = Wl; a.b_ws = ld; a.ldb = d_out;
+        a.C = out; a.c_ws = out_ws; a.ldc = d_out;
+        a.M = b; a.N = d_out; a.K = d_in + 1;
+        a.k_per_split = (a.K + 63) / 64 * 64;
+        const bool vec = mult4(ld) && mult4(d_in) && mult4(d_out) && aligned16(Wl);
+        if (relu) launch_gemm<K_CONTIG, MN_CONTIG, EPI_RELU>(a, vec, true, s);
+        else launch_gemm<K_CONTIG, MN_CONTIG, EPI_NONE>(a, vec, true, s);
+    } else if (kind == 1) {     // [dW ; db] = [A 1]^T dZ
+        a.A = A; a.a_ws = (size_t)b * d_in; a.lda = d_in; a.a_lim = d_in; a.a_ones = d_in;
+        a.B = dZ; a.b_ws = (size_t)b * d_out; a.ldb = d_out;
+        a.C = out; a.c_ws = out_ws; a.ldc = d_out;
+        a.M = d_in + 1; a.N = d_out; a.K = b;
+        a.k_per_split = (a.K + 63) / 64 * 64;
+        launch_gemm<MN_CONTIG, MN_CONTIG, EPI_NONE>(a, mult4(d_in) && mult4(d_out), false, s);
+    } else {                    // dA = (dZ W^T) where A > 0
+        a.A = dZ; a.a_ws = (size_t)b * d_out; a.lda = d_out; a.a_lim = d_out; a.a_ones = -1;
+        a.B = Wl; a.b_ws = ld; a.ldb = d_out;
+        a.C = out; a.c_ws = out_ws; a.ldc = d_in;
+        a.mask = A; a.mask_ws = (size_t)b * d_in; a.ldmask = d_in;
+        a.M = b; a.N = d_in; a.K = d_out;
+        a.k_per_split = (a.K + 63) / 64 * 64;
+        launch_gemm<K_CONTIG, K_CONTIG, EPI_MASK>(a, mult4(ld) && mult4(d_out) && aligned16(Wl), false, s);
+    }
+    return check_launch(name);
+}

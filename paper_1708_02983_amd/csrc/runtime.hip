@@ -37,13 +37,21 @@ Options &options()
     return o;
 }
 
+std::atomic<unsigned long long> &launch_counter()
+{
+    static std::atomic<unsigned long long> n{0};
+    return n;
+}
+
 }  // namespace easgd
 
 extern "C" {
 
 const char *easgd_last_error(void) { return easgd::g_err; }
 
-int easgd_version(void) { return 400; }
+int easgd_version(void) { return 410; }
+
+unsigned long long easgd_launch_count(void) { return easgd::launch_counter().load(std::memory_order_relaxed); }
 
 int easgd_set_option(int option, long value)
 {

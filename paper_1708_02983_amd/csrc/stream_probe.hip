@@ -24,6 +24,20 @@ __global__ __launch_bounds__(256) void stream_triad_kernel(f32x4 *__restrict__ a
         __builtin_nontemporal_store(__builtin_nontemporal_load(b + j) + s * __builtin_nontemporal_load(c + j), a + j);
 }
 
+// a[j] = c[j] + s*d[j], b[j] = d[j] + s*e[j]: three reads and two writes per element, the mix of the momentum update
+__global__ __launch_bounds__(256) void stream_mix32_kernel(f32x4 *__restrict__ a, f32x4 *__restrict__ b,
+                                                           const f32x4 *__restrict__ c, const f32x4 *__restrict__ d,
+                                                           const f32x4 *__restrict__ e, float s, size_t n4)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < n4; j += stride) {
+        const f32x4 x = __builtin_nontemporal_load(c + j), y = __builtin_nontemporal_load(d + j),
+                    z = __builtin_nontemporal_load(e + j);
+        __builtin_nontemporal_store(x + s * y, a + j);
+        __builtin_nontemporal_store(y + s * z, b + j);
+    }
+}
+
 static int probe_grid(size_t n4, dim3 &grid)
 {
     size_t blocks = (n4 + 255) / 256;
@@ -44,7 +58,7 @@ int easgd_stream_copy(float *dst, const float *src, size_t n, void *stream)
     clear_error();
     dim3 grid;
     probe_grid(n / 4, grid);
-    hipLaunchKernelGGL(stream_copy_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)dst, (const f32x4 *)src, n / 4);
+    EASGD_LAUNCH(stream_copy_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)dst, (const f32x4 *)src, n / 4);
     return check_launch("easgd_stream_copy");
 }
 
@@ -56,8 +70,22 @@ int easgd_stream_triad(float *a, const float *b, const float *c, size_t n, float
     clear_error();
     dim3 grid;
     probe_grid(n / 4, grid);
-    hipLaunchKernelGGL(stream_triad_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)a, (const f32x4 *)b, (const f32x4 *)c, s, n / 4);
+    EASGD_LAUNCH(stream_triad_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)a, (const f32x4 *)b, (const f32x4 *)c, s, n / 4);
     return check_launch("easgd_stream_triad");
+}
+
+int easgd_stream_mix32(float *a, float *b, const float *c, const float *d, const float *e, size_t n, float s, void *stream)
+{
+    using namespace easgd;
+    if (!a || !b || !c || !d || !e || n == 0 || (n & 3u) || !aligned16(a) || !aligned16(b) || !aligned16(c) ||
+        !aligned16(d) || !aligned16(e))
+        return fail(EASGD_EINVAL, "easgd_stream_mix32: need non-NULL 16-byte aligned pointers and n %% 4 == 0, n > 0");
+    clear_error();
+    dim3 grid;
+    probe_grid(n / 4, grid);
+    EASGD_LAUNCH(stream_mix32_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)a, (f32x4 *)b,
+                 (const f32x4 *)c, (const f32x4 *)d, (const f32x4 *)e, s, n / 4);
+    return check_launch("easgd_stream_mix32");
 }
 
 }  // extern "C"

@@ -29,3 +29,13 @@ def read_golden(name):
 @pytest.fixture(scope="session")
 def golden():
     return read_golden
+
+
+@pytest.fixture
+def progress(capsys):
+    """Progress lines that reach the terminal while the test runs (past pytest's capture): a long test that stays
+    silent for minutes looks hung to whoever watches the run."""
+    def say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+    return say

@@ -36,7 +36,17 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 NEAR_REL = 1e-5
 
 
-def match_gradient(g_gpu, dims, w, X, y, tol, near_rel=NEAR_REL, max_ties=14):
+def oracle_gradient_base(dims, w, X, y, near_rel):
+    """The oracle's gradient of one worker with its near-zero ReLU gates (|z| <= near_rel * max|Z_layer|) and their
+    ratios |z| / max|Z_layer|: what match_gradient starts from.  Computed once when the same state is matched
+    against two GPU results (teacher-forced and free-running rounds start from the same oracle state)."""
+    import oracle
+    near, ratio = [], []
+    g_ref, loss_ref = oracle.mlp_grad(dims, w, X, y, near_zero=near, near_zero_rel=near_rel, near_zero_ratio=ratio)
+    return g_ref, loss_ref, near, ratio, near_rel
+
+
+def match_gradient(g_gpu, dims, w, X, y, tol, near_rel=NEAR_REL, max_ties=14, base=None):
     """GPU gradient of one worker against the oracle.  Hidden units whose pre-activation is within
     rounding of zero (|z| <= near_rel * max|Z_layer|, judged on the oracle's own z) have a ReLU gate
     that either side may decide either way; if the plain comparison fails, the oracle is re-evaluated
@@ -51,8 +61,11 @@ def match_gradient(g_gpu, dims, w, X, y, tol, near_rel=NEAR_REL, max_ties=14):
     import oracle
     sl = oracle.layer_slices(dims)
     N = sl[-1][1].stop
-    near = []
-    g_ref, loss_ref = oracle.mlp_grad(dims, w, X, y, near_zero=near, near_zero_rel=near_rel)
+    if base is None:
+        base = oracle_gradient_base(dims, w, X, y, near_rel)
+    assert base[4] >= near_rel
+    g_ref, loss_ref = base[0], base[1]
+    near = [t for t, r in zip(base[2], base[3]) if r <= near_rel]
     plain = normwise(g_gpu[:N], g_ref)
     if plain <= tol:
         return g_ref, loss_ref, 0
@@ -89,15 +102,17 @@ def match_gradient(g_gpu, dims, w, X, y, tol, near_rel=NEAR_REL, max_ties=14):
     return g_best, loss_ref, len(flips)
 
 
-def match_gradients_all_workers(G_gpu, dims, W, X, y, tol, near_rel=NEAR_REL):
-    """match_gradient for every worker: oracle G[P][ld] (NaN padding), losses, total flipped gates."""
+def match_gradients_all_workers(G_gpu, dims, W, X, y, tol, near_rel=NEAR_REL, bases=None):
+    """match_gradient for every worker: oracle G[P][ld] (NaN padding), losses, total flipped gates.
+    bases: per worker what oracle_gradient_base returned for this state (with a near_rel at least as wide)."""
     P, ld = W.shape
     G = np.full((P, ld), np.nan, dtype=np.float32)
     N = None
     loss = np.zeros(P)
     flips = 0
     for i in range(P):
-        g, loss[i], k = match_gradient(G_gpu[i], dims, W[i], X[i], y[i], tol, near_rel)
+        g, loss[i], k = match_gradient(G_gpu[i], dims, W[i], X[i], y[i], tol, near_rel,
+                                       base=None if bases is None else bases[i])
         G[i, :g.shape[0]] = g
         flips += k
     return G, loss, flips

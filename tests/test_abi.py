@@ -29,7 +29,8 @@ def test_every_declared_symbol_is_exported(lib):
             "easgd_mlp_num_params", "easgd_last_error", "easgd_version", "easgd_set_option",
             "easgd_get_option", "easgd_stream_copy", "easgd_stream_triad", "easgd_mlp_round", "easgd_mlp_round_bf16v",
             "easgd_mlp_round_workspace_bytes", "easgd_sync_round_bf16", "measgd_round_bf16", "measgd_round_bf16v",
-            "easgd_grad_bf16", "easgd_grad_static", "sync_sgd_round"} <= set(names)
+            "easgd_grad_bf16", "easgd_grad_static", "sync_sgd_round", "easgd_stream_mix32",
+            "easgd_launch_count", "easgd_layer_product"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/easgd.h but not exported"
 
@@ -78,7 +79,23 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert lib.easgd_sync_round_bf16(fake, None, fake, 1, 4, 4, 0.1, 0.1, None) == -1
     assert lib.easgd_sync_round_bf16(fake, fake, fake, 1, 8, 4, 0.1, 0.1, None) == -1
     assert b"easgd_sync_round_bf16" in lib.easgd_last_error()
+    # pointers that are not aligned to their element type are rejected (fp32: 4 bytes, bfloat16: 2 bytes)
+    for bad in (0x1001, 0x1002):
+        assert lib.easgd_sync_round(bad, fake, fake, 1, 4, 4, 0.1, 0.1, None) == -1
+        assert b"4-byte aligned" in lib.easgd_last_error()
+        assert lib.easgd_sync_round(fake, bad, fake, 1, 4, 4, 0.1, 0.1, None) == -1
+        assert lib.easgd_sync_round(fake, fake, bad, 1, 4, 4, 0.1, 0.1, None) == -1
+        assert lib.measgd_round(fake, bad, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+        assert lib.measgd_round_bf16v(fake, fake, bad, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+        assert lib.measgd_round_bf16(bad, fake, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+    assert lib.measgd_round_bf16(fake, 0x1001, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+    assert b"2-byte aligned" in lib.easgd_last_error()
+    assert lib.measgd_round_bf16(fake, fake, 0x1001, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+    assert lib.measgd_round_bf16v(fake, 0x1003, fake, fake, 1, 4, 4, 0.1, 0.1, 0.9, None) == -1
+    assert lib.easgd_sync_round_bf16(fake, 0x1001, fake, 1, 4, 4, 0.1, 0.1, None) == -1
     lib.sync_sgd_round.argtypes = [vp, vp, vp, ctypes.c_int, sz, sz, f, f, vp]
+    assert lib.sync_sgd_round(0x1002, None, fake, 1, 4, 4, 0.1, 0.0, None) == -1
+    assert lib.sync_sgd_round(fake, 0x1001, fake, 1, 4, 4, 0.1, 0.9, None) == -1
     assert lib.sync_sgd_round(None, None, fake, 1, 4, 4, 0.1, 0.0, None) == -1
     assert lib.sync_sgd_round(fake, None, None, 1, 4, 4, 0.1, 0.0, None) == -1
     assert lib.sync_sgd_round(fake, None, fake, 0, 4, 4, 0.1, 0.0, None) == -1

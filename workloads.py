@@ -154,6 +154,24 @@ def update_gradients(P: int, N: int, t: int, ld: Optional[int] = None, seed: int
     return G
 
 
+def host_normal_rows(P: int, N: int, std: float, stream: int, seed: int = DEFAULT_SEED, threads: int = 8) -> np.ndarray:
+    """[P][N] fp32 draws of N(0, std) in host memory, filled by several threads (one Philox stream per chunk):
+    full-size update-only inputs for a host-side run, where a single stream would take a minute."""
+    from concurrent.futures import ThreadPoolExecutor
+    out = np.empty((P, N), dtype=np.float32)
+    step = max(N // 4 + 1, 1)
+
+    def fill(job):
+        i, lo = job
+        hi = min(lo + step, N)
+        _rng(seed, stream, i, lo).standard_normal(out=out[i, lo:hi], dtype=np.float32)
+        out[i, lo:hi] *= np.float32(std)
+
+    with ThreadPoolExecutor(max(1, threads)) as ex:
+        list(ex.map(fill, [(i, lo) for i in range(P) for lo in range(0, N, step)]))
+    return out
+
+
 # --------------------------------------------------------------------------
 # Full-size update-only inputs drawn directly in device memory.
 # torch is used purely as a seeded random-number source here.

@@ -79,6 +79,7 @@ def _sum_ms(starts, stops):
     return float(sum(a.elapsed_time(b) for a, b in zip(starts, stops)))
 
 
+UPDATE_LD_ALIGN = 256          # elements: replica rows of the update-only workloads start on 1 KiB boundaries
 PREROLL_MIN_S = 0.25
 PREROLL_MAX_S = 2.0
 
@@ -264,26 +265,29 @@ def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
     workload's update with gradients and momentum buffers stored as bfloat16 (an extension)."""
     import torch
     P, N = wl.P, wl.N
-    dW = workloads.device_normal((P, N), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 1)
+    # replica rows start on 1 KiB boundaries (ld = N rounded up to 256 elements; the padding is never touched): the
+    # kernels' 1 KiB pieces then coincide with aligned KiB of every row, worth 2-4 % over ld = N
+    ld = workloads.round_up(N, UPDATE_LD_ALIGN)
+    dW = workloads.device_normal((P, ld), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 1)
     dWc = workloads.device_normal((N,), workloads.WEIGHT_STD, workloads.DEFAULT_SEED, 2)
     dV = torch.zeros_like(dW) if wl.momentum else None
     # gradients of consecutive rounds: a small pool of independent draws, cycled (footprint >> caches)
-    Gs = [workloads.device_normal((P, N), workloads.GRADIENT_STD, workloads.DEFAULT_SEED, 100 + t) for t in range(pool)]
+    Gs = [workloads.device_normal((P, ld), workloads.GRADIENT_STD, workloads.DEFAULT_SEED, 100 + t) for t in range(pool)]
     if rule == "elastic_bf16":
         Gs = [g.to(torch.bfloat16) for g in Gs]
-        dV = torch.zeros((P, N), dtype=torch.bfloat16, device="cuda") if wl.momentum else None
+        dV = torch.zeros((P, ld), dtype=torch.bfloat16, device="cuda") if wl.momentum else None
 
     def step(t):
         if rule == "elastic_bf16" and wl.momentum:
-            hip.measgd_round_bf16(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta)
+            hip.measgd_round_bf16(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta, N=N)
         elif rule == "elastic_bf16":
-            hip.easgd_sync_round_bf16(dW, Gs[t % pool], dWc, wl.eta, wl.rho)
+            hip.easgd_sync_round_bf16(dW, Gs[t % pool], dWc, wl.eta, wl.rho, N=N)
         elif rule == "sync_sgd":
-            hip.sync_sgd_round(dW, Gs[t % pool], wl.eta / P, V=dV, delta=wl.delta or 0.0)
+            hip.sync_sgd_round(dW, Gs[t % pool], wl.eta / P, V=dV, delta=wl.delta or 0.0, N=N)
         elif wl.momentum:
-            hip.measgd_round(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta)
+            hip.measgd_round(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta, N=N)
         else:
-            hip.easgd_sync_round(dW, Gs[t % pool], dWc, wl.eta, wl.rho)
+            hip.easgd_sync_round(dW, Gs[t % pool], dWc, wl.eta, wl.rho, N=N)
 
     done, pre = preroll(step, 20)
     for t in range(warmup):
@@ -343,7 +347,8 @@ TRAFFIC_PROFILED_VERSION = 330      # easgd_version() of the library the summari
 def traffic_fields(hip, key):
     """`traffic` (bytes per launch) and its provenance for a roofline object; None when the profile is stale."""
     entry = TRAFFIC_PROFILES.get(key)
-    default_opts = (hip.get_option(hip.OPT_UPDATE_GROUPS) == 4 and hip.get_option(hip.OPT_UPDATE_NONTEMPORAL) == 1
+    default_opts = (hip.get_option(hip.OPT_UPDATE_GROUPS) == 0 and hip.get_option(hip.OPT_UPDATE_LAYOUT) == 2
+                    and hip.get_option(hip.OPT_UPDATE_NONTEMPORAL) == 1
                     and hip.get_option(hip.OPT_UPDATE_BLOCKS_PER_CU) == 0 and hip.get_option(hip.OPT_GEMM_TILE) == 0)
     if entry is None or not default_opts or hip.version() != TRAFFIC_PROFILED_VERSION:
         return {"traffic": None}
@@ -510,8 +515,9 @@ def training_report(hip, wl, steps, warmup, name, full):
     return out
 
 
-def mix32_ceiling(hip, n=366_000_000, reps=20):
-    """Attainable HBM bandwidth (GB/s) for a 3-read/2-write stream, the mix of the momentum update."""
+def mix32_ceiling(hip, n=600_000_000, reps=12):
+    """Attainable HBM bandwidth (GB/s) for a 3-read/2-write stream, the mix of the momentum update, over five
+    arrays of 2.4 GB (12 GB in all, the footprint of cfg5)."""
     import torch
     bufs = [torch.ones(n, dtype=torch.float32, device="cuda") for _ in range(5)]
     for _ in range(3):

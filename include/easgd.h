@@ -313,7 +313,8 @@ size_t easgd_mlp_num_params(const int *dims, int n_layers);
 typedef enum {
     EASGD_OPT_UPDATE_BLOCKS_PER_CU = 1,  /* 0 = one block per tile (default); k>0 = persistent grid of k*CUs blocks */
     EASGD_OPT_UPDATE_NONTEMPORAL   = 2,  /* 1 = streaming (non-temporal) loads/stores for W, G, V (default), 0 = plain */
-    EASGD_OPT_UPDATE_GROUPS        = 3,  /* 128-bit groups per thread and worker: 1, 2 or 4 (default); tile = groups*1024 parameters */
+    EASGD_OPT_UPDATE_GROUPS        = 3,  /* 128-bit groups per thread and worker: 1, 2, 4 or 8; 0 = chosen per call (default): 4, or 8
+                                            for the rules that stream three arrays per worker, fewer when N is small */
     EASGD_OPT_GEMM_TILE            = 4,  /* block tile of the wide matrix products of easgd_grad: 0 = chosen per product (default),
                                             1 = 128x128, 2 = 64x64, 3 = 128x64 */
     EASGD_OPT_ROUND_OVERLAP        = 5,  /* easgd_mlp_round, where the center rule runs: 0 = a kernel of its own on the caller's
@@ -327,9 +328,13 @@ typedef enum {
                                             (default); 2 = the same without that interleaving; 0 = plain block order */
     EASGD_OPT_GEMM_PAIR            = 7,  /* 1 = independent products of backward propagation share a launch where their tile
                                             shapes allow (default), 0 = one launch per product */
-    EASGD_OPT_MLP_HEAD             = 8   /* 1 = a last layer of at most 16 classes takes one launch for its forward product, the
+    EASGD_OPT_MLP_HEAD             = 8,  /* 1 = a last layer of at most 16 classes takes one launch for its forward product, the
                                             softmax cross-entropy and its input-gradient product (default), 0 = three launches
                                             (split-K product, softmax, product) */
+    EASGD_OPT_UPDATE_LAYOUT        = 9   /* which parameters a block of the streaming update kernels owns: 0 = a contiguous run of
+                                            groups*1024 parameters; 1 = eight consecutive blocks (one per die) interleave in pieces
+                                            of 1 KiB inside a super-tile, so that every die's requests spread over all memory
+                                            channels; 2 = chosen per call (default): 1 when N is large enough for 4 groups */
 } easgd_option;
 
 int easgd_set_option(int option, long value);

@@ -26,6 +26,7 @@ OPT_ROUND_OVERLAP = 5
 OPT_GEMM_XCD = 6
 OPT_GEMM_PAIR = 7
 OPT_MLP_HEAD = 8
+OPT_UPDATE_LAYOUT = 9
 
 
 class EasgdError(RuntimeError):

@@ -7,13 +7,15 @@
 // read once and every result written once: this kernel is a pure HBM stream of
 // N*(12P+8) bytes (EASGD) or N*(20P+8) bytes (momentum).
 //
-// A block owns a tile of GROUPS*256 groups of four consecutive parameters
-// (GROUPS*4 KiB contiguous in every stream) and walks the workers one at a
-// time: for worker i every thread issues its GROUPS 128-bit loads of W_i and
-// G_i (and V_i) back to back, applies the rule and stores.  At any moment a
-// block touches the streams of ONE worker, in runs of GROUPS*4 KiB; measured
-// on MI355X this is 2-5 % faster than having every thread interleave several
-// workers (HBM efficiency drops as more address streams are active at once).
+// A block of 256 threads owns GROUPS*256 groups of four consecutive parameters
+// and walks the workers one at a time: for worker i every thread issues its
+// GROUPS 128-bit loads of W_i and G_i (and V_i) back to back, applies the rule
+// and stores.  At any moment a block touches the streams of ONE worker;
+// measured on MI355X this is 2-5 % faster than having every thread interleave
+// several workers (HBM efficiency drops as more address streams are active at
+// once).  Which groups a block owns is the TileMap of common.h: for large N the
+// eight dies interleave at 1 KiB granularity inside super-tiles instead of
+// each streaming contiguous runs of its own, worth 10-18 % of bandwidth.
 #include "common.h"
 #include "elastic_rule.h"
 
@@ -72,57 +74,75 @@ __device__ __forceinline__ void elastic_group(T *__restrict__ W, T *__restrict__
     Wc[j] = c + alpha * acc;                  // Eq. (2)
 }
 
-// 128-bit path.  Tiles of GROUPS*256 groups; the N % 4 tail elements are handled as scalars by the last block.
-template <bool MOM, bool NT, int GROUPS>
+// One tile of the 128-bit path: thread-owned groups j0 + q*STRIDE.  FULL: every group of the block lies inside the
+// row (the block-uniform common case): no per-lane guards, so all 2*GROUPS (3*GROUPS) loads of a worker are in
+// flight together.  Guarded loads would be waited for group by group (a guarded value is a merge of two
+// definitions, and the wait lands at the merge).
+template <bool MOM, bool NT, int GROUPS, size_t STRIDE, bool FULL>
+__device__ __forceinline__ void elastic_tile(f32x4 *__restrict__ W, f32x4 *__restrict__ V, const f32x4 *__restrict__ G,
+                                             f32x4 *__restrict__ Wc, int P, size_t n4, size_t ld4, size_t j0,
+                                             float eta, float rho, float alpha, float delta)
+{
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 c[GROUPS], acc[GROUPS];
+#pragma unroll
+    for (int q = 0; q < GROUPS; ++q) {
+        const size_t j = j0 + (size_t)q * STRIDE;
+        c[q] = (FULL || j < n4) ? Wc[j] : zero;       // the "broadcast" of the center, once per parameter
+        acc[q] = zero;
+    }
+    for (int i = 0; i < P; ++i) {                     // ascending worker order: fixed summation order
+        const size_t row = (size_t)i * ld4;
+        f32x4 w[GROUPS], g[GROUPS], v[GROUPS];
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) {
+                w[q] = stream_load<NT>(W + row + j);
+                g[q] = stream_load<NT>(G + row + j);
+                if constexpr (MOM) v[q] = stream_load<NT>(V + row + j);
+            }
+        }
+        // every load of this worker is issued before the first result is used: the scheduler otherwise pairs
+        // loads with the arithmetic of earlier groups to save registers and waits for them one by one
+        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) {
+                acc[q] += worker_rule<MOM>(w[q], v[q], g[q], c[q], eta, rho, alpha, delta);
+                stream_store<NT>(W + row + j, w[q]);
+                if constexpr (MOM) stream_store<NT>(V + row + j, v[q]);
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < GROUPS; ++q) {
+        const size_t j = j0 + (size_t)q * STRIDE;
+        if (FULL || j < n4) Wc[j] = c[q] + alpha * acc[q];   // Eq. (2)
+    }
+}
+
+// 128-bit path.  The N % 4 tail elements are handled as scalars by the last block.
+template <bool MOM, bool NT, int GROUPS, bool DIES>
 __global__ __launch_bounds__(256) void elastic_vec4_kernel(float *__restrict__ Wp, float *__restrict__ Vp,
                                                            const float *__restrict__ Gp, float *__restrict__ Wcp,
                                                            int P, size_t N, size_t ld,
                                                            float eta, float rho, float alpha, float delta)
 {
+    typedef TileMap<GROUPS, DIES> Map;
     f32x4 *__restrict__ W = (f32x4 *)Wp;
     f32x4 *__restrict__ V = (f32x4 *)Vp;
     const f32x4 *__restrict__ G = (const f32x4 *)Gp;
     f32x4 *__restrict__ Wc = (f32x4 *)Wcp;
     const size_t n4 = N / 4, ld4 = ld / 4;
-    constexpr size_t TILE = (size_t)GROUPS * 256;
-    const size_t n_tiles = (n4 + TILE - 1) / TILE;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const size_t n_tiles = Map::tiles(n4);
     for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const size_t j0 = t * TILE + threadIdx.x;
-        f32x4 c[GROUPS], acc[GROUPS];
-#pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * 256;
-            c[q] = (j < n4) ? Wc[j] : zero;           // the "broadcast" of the center, once per parameter
-            acc[q] = zero;
-        }
-        for (int i = 0; i < P; ++i) {                 // ascending worker order: fixed summation order
-            const size_t row = (size_t)i * ld4;
-            f32x4 w[GROUPS], g[GROUPS], v[GROUPS];
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * 256;
-                if (j < n4) {
-                    w[q] = stream_load<NT>(W + row + j);
-                    g[q] = stream_load<NT>(G + row + j);
-                    if constexpr (MOM) v[q] = stream_load<NT>(V + row + j);
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * 256;
-                if (j < n4) {
-                    acc[q] += worker_rule<MOM>(w[q], v[q], g[q], c[q], eta, rho, alpha, delta);
-                    stream_store<NT>(W + row + j, w[q]);
-                    if constexpr (MOM) stream_store<NT>(V + row + j, v[q]);
-                }
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * 256;
-            if (j < n4) Wc[j] = c[q] + alpha * acc[q];   // Eq. (2)
-        }
+        const size_t j0 = Map::first(t, threadIdx.x);
+        if (Map::last(t) < n4)                        // uniform for the block
+            elastic_tile<MOM, NT, GROUPS, Map::STRIDE, true>(W, V, G, Wc, P, n4, ld4, j0, eta, rho, alpha, delta);
+        else
+            elastic_tile<MOM, NT, GROUPS, Map::STRIDE, false>(W, V, G, Wc, P, n4, ld4, j0, eta, rho, alpha, delta);
     }
     const size_t tail = N - n4 * 4;
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail)
@@ -185,14 +205,15 @@ __global__ __launch_bounds__(256) void elastic_scalar_kernel(float *__restrict__
         elastic_group<MOM, false, 4, float>(W, V, G, Wc, P, j, ld, eta, rho, alpha, delta);
 }
 
-template <bool MOM, bool NT>
+template <bool MOM, bool NT, bool DIES>
 static void launch_vec4(int groups, dim3 grid, hipStream_t s, float *W, float *V, const float *G, float *Wc,
                         int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
 {
     switch (groups) {
-    case 1: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    case 2: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    default: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 1: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 1, DIES>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 2: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 2, DIES>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 4: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 4, DIES>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    default: EASGD_LAUNCH((elastic_vec4_kernel<MOM, NT, 8, DIES>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
     }
 }
 
@@ -213,26 +234,23 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
     hipStream_t s = static_cast<hipStream_t>(stream);
     const float alpha = eta * rho;            // elastic coefficient of workers and center
     const bool vec = aligned16(W) && aligned16(G) && aligned16(Wc) && (!MOM || aligned16(V)) && (ld % 4 == 0);
-    // vector path: one block per tile of groups*256 groups (the scalar tail rides on the last block)
-    // fewer groups per thread for small N, so that the grid still covers the chip several times
-    size_t groups = (size_t)opt.update_groups;
-    while (groups > 1 && N / 4 / (groups * 256) < (size_t)(4 * num_cus())) groups /= 2;
-    size_t blocks = vec ? (N / 4 + groups * 256 - 1) / (groups * 256) : (N + 255) / 256;
-    if (blocks == 0) blocks = 1;
-    if (opt.update_blocks_per_cu > 0) {
-        const size_t persistent = (size_t)opt.update_blocks_per_cu * (size_t)num_cus();
-        if (blocks > persistent) blocks = persistent;
-    }
+    // vector path: groups per thread, tile map and grid (the scalar tail rides on the last block)
+    const UpdateShape shape = update_shape(N, MOM);
+    size_t blocks = vec ? shape.blocks : (N + 255) / 256;
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loop covers the rest
     const dim3 grid((unsigned)blocks);
+    const int groups = shape.groups;
     // few parameters and several workers: split the workers over the wavefronts of a block
     const bool split = vec && P >= 4 && (N / 4 + 255) / 256 < (size_t)(2 * num_cus());
     if (split) {
         const dim3 split_grid((unsigned)((N / 4 + 63) / 64 > 0 ? (N / 4 + 63) / 64 : 1));
         EASGD_LAUNCH((elastic_split_kernel<MOM>), split_grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     } else if (vec) {
-        if (opt.update_nontemporal) launch_vec4<MOM, true>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
-        else launch_vec4<MOM, false>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        const bool nt = opt.update_nontemporal != 0;
+        if (shape.dies && nt) launch_vec4<MOM, true, true>(groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        else if (shape.dies) launch_vec4<MOM, false, true>(groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        else if (nt) launch_vec4<MOM, true, false>(groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        else launch_vec4<MOM, false, false>(groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     } else {
         EASGD_LAUNCH((elastic_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     }
@@ -276,55 +294,66 @@ __device__ __forceinline__ void sgd_rule(T &w, T &v, T s, float eta, float mu)
     }
 }
 
-template <bool MOM, bool NT, int GROUPS>
+// One tile of the 128-bit path (FULL as in elastic_tile).
+template <bool MOM, bool NT, int GROUPS, size_t STRIDE, bool FULL>
+__device__ __forceinline__ void sync_sgd_tile(f32x4 *__restrict__ W, f32x4 *__restrict__ V, const f32x4 *__restrict__ G,
+                                              int P, size_t n4, size_t ld4, size_t j0, float eta, float mu)
+{
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 s[GROUPS];
+#pragma unroll
+    for (int q = 0; q < GROUPS; ++q) s[q] = zero;
+    for (int i = 0; i < P; ++i) {                     // ascending worker order: fixed summation order
+        const size_t row = (size_t)i * ld4;
+        f32x4 g[GROUPS];
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            g[q] = (FULL || j < n4) ? stream_load<NT>(G + row + j) : zero;
+        }
+        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) s[q] += g[q];
+    }
+    for (int i = 0; i < P; ++i) {
+        const size_t row = (size_t)i * ld4;
+        f32x4 w[GROUPS], v[GROUPS];
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) {
+                w[q] = stream_load<NT>(W + row + j);
+                if constexpr (MOM) v[q] = stream_load<NT>(V + row + j);
+            }
+        }
+        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);     // all loads of this replica before the first use
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) {
+                sgd_rule<MOM>(w[q], v[q], s[q], eta, mu);
+                stream_store<NT>(W + row + j, w[q]);
+                if constexpr (MOM) stream_store<NT>(V + row + j, v[q]);
+            }
+        }
+    }
+}
+
+template <bool MOM, bool NT, int GROUPS, bool DIES>
 __global__ __launch_bounds__(256) void sync_sgd_vec4_kernel(float *__restrict__ Wp, float *__restrict__ Vp,
                                                             const float *__restrict__ Gp, int P, size_t N, size_t ld,
                                                             float eta, float mu)
 {
+    typedef TileMap<GROUPS, DIES> Map;
     f32x4 *__restrict__ W = (f32x4 *)Wp;
     f32x4 *__restrict__ V = (f32x4 *)Vp;
     const f32x4 *__restrict__ G = (const f32x4 *)Gp;
     const size_t n4 = N / 4, ld4 = ld / 4;
-    constexpr size_t TILE = (size_t)GROUPS * 256;
-    const size_t n_tiles = (n4 + TILE - 1) / TILE;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const size_t n_tiles = Map::tiles(n4);
     for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const size_t j0 = t * TILE + threadIdx.x;
-        f32x4 s[GROUPS];
-#pragma unroll
-        for (int q = 0; q < GROUPS; ++q) s[q] = zero;
-        for (int i = 0; i < P; ++i) {                 // ascending worker order: fixed summation order
-            const size_t row = (size_t)i * ld4;
-            f32x4 g[GROUPS];
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * 256;
-                g[q] = (j < n4) ? stream_load<NT>(G + row + j) : zero;
-            }
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) s[q] += g[q];
-        }
-        for (int i = 0; i < P; ++i) {
-            const size_t row = (size_t)i * ld4;
-            f32x4 w[GROUPS], v[GROUPS];
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * 256;
-                if (j < n4) {
-                    w[q] = stream_load<NT>(W + row + j);
-                    if constexpr (MOM) v[q] = stream_load<NT>(V + row + j);
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * 256;
-                if (j < n4) {
-                    sgd_rule<MOM>(w[q], v[q], s[q], eta, mu);
-                    stream_store<NT>(W + row + j, w[q]);
-                    if constexpr (MOM) stream_store<NT>(V + row + j, v[q]);
-                }
-            }
-        }
+        const size_t j0 = Map::first(t, threadIdx.x);
+        if (Map::last(t) < n4) sync_sgd_tile<MOM, NT, GROUPS, Map::STRIDE, true>(W, V, G, P, n4, ld4, j0, eta, mu);
+        else sync_sgd_tile<MOM, NT, GROUPS, Map::STRIDE, false>(W, V, G, P, n4, ld4, j0, eta, mu);
     }
     const size_t tail = N - n4 * 4;
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail) {
@@ -358,13 +387,14 @@ __global__ __launch_bounds__(256) void sync_sgd_scalar_kernel(float *__restrict_
     }
 }
 
-template <bool MOM, bool NT>
+template <bool MOM, bool NT, bool DIES>
 static void launch_sync_sgd(int groups, dim3 grid, hipStream_t s, float *W, float *V, const float *G, int P, size_t N,
                             size_t ld, float eta, float mu)
 {
-    if (groups == 4) EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 4>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
-    else if (groups == 2) EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 2>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
-    else EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 1>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    if (groups >= 8) EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 8, DIES>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else if (groups == 4) EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 4, DIES>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else if (groups == 2) EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 2, DIES>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
+    else EASGD_LAUNCH((sync_sgd_vec4_kernel<MOM, NT, 1, DIES>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
 }
 
 template <bool MOM>
@@ -381,15 +411,16 @@ static int sync_sgd(float *W, float *V, const float *G, int P, size_t N, size_t 
     const Options &opt = options();
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = aligned16(W) && aligned16(G) && (!MOM || aligned16(V)) && (ld % 4 == 0);
-    size_t groups = (size_t)opt.update_groups;
-    while (groups > 1 && N / 4 / (groups * 256) < (size_t)(4 * num_cus())) groups /= 2;
-    size_t blocks = vec ? (N / 4 + groups * 256 - 1) / (groups * 256) : (N + 255) / 256;
-    if (blocks == 0) blocks = 1;
+    const UpdateShape shape = update_shape(N, MOM);
+    size_t blocks = vec ? shape.blocks : (N + 255) / 256;
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
     const dim3 grid((unsigned)blocks);
+    const bool nt = opt.update_nontemporal != 0;
     if (!vec) EASGD_LAUNCH((sync_sgd_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
-    else if (opt.update_nontemporal) launch_sync_sgd<MOM, true>((int)groups, grid, s, W, V, G, P, N, ld, eta, mu);
-    else launch_sync_sgd<MOM, false>((int)groups, grid, s, W, V, G, P, N, ld, eta, mu);
+    else if (shape.dies && nt) launch_sync_sgd<MOM, true, true>(shape.groups, grid, s, W, V, G, P, N, ld, eta, mu);
+    else if (shape.dies) launch_sync_sgd<MOM, false, true>(shape.groups, grid, s, W, V, G, P, N, ld, eta, mu);
+    else if (nt) launch_sync_sgd<MOM, true, false>(shape.groups, grid, s, W, V, G, P, N, ld, eta, mu);
+    else launch_sync_sgd<MOM, false, false>(shape.groups, grid, s, W, V, G, P, N, ld, eta, mu);
     return check_launch(name);
 }
 

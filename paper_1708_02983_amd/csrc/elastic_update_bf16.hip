@@ -59,69 +59,85 @@ template <typename T> struct Vec4;
 template <> struct Vec4<float> { typedef f32x4 type; };
 template <> struct Vec4<unsigned short> { typedef u16x4 type; };
 
-// 128-bit accesses to the fp32 rows, 64-bit accesses to the bfloat16 rows.  The N % 4 tail rides on the last block.
+// One tile: 128-bit accesses to the fp32 rows, 64-bit accesses to the bfloat16 rows.  FULL: every group of the block
+// lies inside the row (block-uniform), so no load is guarded and all loads of a worker are in flight together.
 // GT: storage type of the gradients (unsigned short = bfloat16, or float when only V is stored in 16 bits).
-template <bool MOM, bool NT, int GROUPS, typename GT>
+template <bool MOM, bool NT, int GROUPS, size_t STRIDE, bool FULL, typename GT>
+__device__ __forceinline__ void elastic_bf16_tile(f32x4 *__restrict__ W, u16x4 *__restrict__ V,
+                                                  const typename Vec4<GT>::type *__restrict__ G, f32x4 *__restrict__ Wc,
+                                                  int P, size_t n4, size_t ld4, size_t j0,
+                                                  float eta, float rho, float alpha, float delta)
+{
+    typedef typename Vec4<GT>::type g4;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 c[GROUPS], acc[GROUPS];
+#pragma unroll
+    for (int q = 0; q < GROUPS; ++q) {
+        const size_t j = j0 + (size_t)q * STRIDE;
+        c[q] = (FULL || j < n4) ? Wc[j] : zero;
+        acc[q] = zero;
+    }
+    for (int i = 0; i < P; ++i) {
+        const size_t row = (size_t)i * ld4;
+        f32x4 w[GROUPS];
+        g4 g[GROUPS];
+        u16x4 v[GROUPS];
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) {
+                w[q] = lp_load<NT>(W + row + j);
+                g[q] = lp_load<NT>(G + row + j);
+                if constexpr (MOM) v[q] = lp_load<NT>(V + row + j);
+            }
+        }
+        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);     // all loads of this worker before the first use
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float we = w[q][e];
+                    unsigned short ve = 0;
+                    if constexpr (MOM) ve = v[q][e];
+                    acc[q][e] += worker_rule_bf16<MOM>(we, ve, grad_value(g[q][e]), c[q][e], eta, rho, alpha, delta);
+                    w[q][e] = we;
+                    if constexpr (MOM) v[q][e] = ve;
+                }
+                lp_store<NT>(W + row + j, w[q]);
+                if constexpr (MOM) lp_store<NT>(V + row + j, v[q]);
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < GROUPS; ++q) {
+        const size_t j = j0 + (size_t)q * STRIDE;
+        if (FULL || j < n4) Wc[j] = c[q] + alpha * acc[q];   // Eq. (2)
+    }
+}
+
+// The N % 4 tail rides on the last block.
+template <bool MOM, bool NT, int GROUPS, bool DIES, typename GT>
 __global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restrict__ Wp, unsigned short *__restrict__ Vp,
                                                                 const GT *__restrict__ Gp,
                                                                 float *__restrict__ Wcp, int P, size_t N, size_t ld,
                                                                 float eta, float rho, float alpha, float delta)
 {
     typedef typename Vec4<GT>::type g4;
+    typedef TileMap<GROUPS, DIES> Map;
     f32x4 *__restrict__ W = (f32x4 *)Wp;
     u16x4 *__restrict__ V = (u16x4 *)Vp;
     const g4 *__restrict__ G = (const g4 *)Gp;
     f32x4 *__restrict__ Wc = (f32x4 *)Wcp;
     const size_t n4 = N / 4, ld4 = ld / 4;
-    constexpr size_t TILE = (size_t)GROUPS * 256;
-    const size_t n_tiles = (n4 + TILE - 1) / TILE;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const size_t n_tiles = Map::tiles(n4);
     for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const size_t j0 = t * TILE + threadIdx.x;
-        f32x4 c[GROUPS], acc[GROUPS];
-#pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * 256;
-            c[q] = (j < n4) ? Wc[j] : zero;
-            acc[q] = zero;
-        }
-        for (int i = 0; i < P; ++i) {
-            const size_t row = (size_t)i * ld4;
-            f32x4 w[GROUPS];
-            g4 g[GROUPS];
-            u16x4 v[GROUPS];
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * 256;
-                if (j < n4) {
-                    w[q] = lp_load<NT>(W + row + j);
-                    g[q] = lp_load<NT>(G + row + j);
-                    if constexpr (MOM) v[q] = lp_load<NT>(V + row + j);
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * 256;
-                if (j < n4) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float we = w[q][e];
-                        unsigned short ve = 0;
-                        if constexpr (MOM) ve = v[q][e];
-                        acc[q][e] += worker_rule_bf16<MOM>(we, ve, grad_value(g[q][e]), c[q][e], eta, rho, alpha, delta);
-                        w[q][e] = we;
-                        if constexpr (MOM) v[q][e] = ve;
-                    }
-                    lp_store<NT>(W + row + j, w[q]);
-                    if constexpr (MOM) lp_store<NT>(V + row + j, v[q]);
-                }
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * 256;
-            if (j < n4) Wc[j] = c[q] + alpha * acc[q];   // Eq. (2)
-        }
+        const size_t j0 = Map::first(t, threadIdx.x);
+        if (Map::last(t) < n4)
+            elastic_bf16_tile<MOM, NT, GROUPS, Map::STRIDE, true, GT>(W, V, G, Wc, P, n4, ld4, j0, eta, rho, alpha, delta);
+        else
+            elastic_bf16_tile<MOM, NT, GROUPS, Map::STRIDE, false, GT>(W, V, G, Wc, P, n4, ld4, j0, eta, rho, alpha, delta);
     }
     const size_t tail = N - n4 * 4;
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail)
@@ -140,14 +156,15 @@ __global__ __launch_bounds__(256) void elastic_bf16_scalar_kernel(float *__restr
         scalar_param<MOM, GT>(W, V, G, Wc, P, j, ld, eta, rho, alpha, delta);
 }
 
-template <bool MOM, bool NT, typename GT>
+template <bool MOM, bool NT, bool DIES, typename GT>
 static void launch_bf16(int groups, dim3 grid, hipStream_t s, float *W, unsigned short *V, const GT *G,
                         float *Wc, int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
 {
     switch (groups) {
-    case 1: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 1, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    case 2: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 2, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    default: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 4, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 1: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 1, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 2: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 2, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 4: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 4, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    default: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 8, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
     }
 }
 
@@ -170,23 +187,21 @@ static int elastic_round_bf16(const char *name, float *W, unsigned short *V, con
     const float alpha = eta * rho;
     const bool g_aligned = sizeof(GT) == 4 ? aligned16(G) : aligned8(G);
     const bool vec = aligned16(W) && aligned16(Wc) && g_aligned && (!MOM || aligned8(V)) && (ld % 4 == 0);
-    // fewer groups per thread for small N, so that the grid still covers the chip several times
-    size_t groups = (size_t)opt.update_groups;
-    while (groups > 1 && N / 4 / (groups * 256) < (size_t)(4 * num_cus())) groups /= 2;
-    size_t blocks = vec ? (N / 4 + groups * 256 - 1) / (groups * 256) : (N + 255) / 256;
-    if (blocks == 0) blocks = 1;
-    if (opt.update_blocks_per_cu > 0) {
-        const size_t persistent = (size_t)opt.update_blocks_per_cu * (size_t)num_cus();
-        if (blocks > persistent) blocks = persistent;
-    }
+    const UpdateShape shape = update_shape(N, MOM);
+    size_t blocks = vec ? shape.blocks : (N + 255) / 256;
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
     const dim3 grid((unsigned)blocks);
+    const bool nt = opt.update_nontemporal != 0;
     if (!vec)
         EASGD_LAUNCH((elastic_bf16_scalar_kernel<MOM, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
-    else if (opt.update_nontemporal)
-        launch_bf16<MOM, true, GT>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    else if (shape.dies && nt)
+        launch_bf16<MOM, true, true, GT>(shape.groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    else if (shape.dies)
+        launch_bf16<MOM, false, true, GT>(shape.groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+    else if (nt)
+        launch_bf16<MOM, true, false, GT>(shape.groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     else
-        launch_bf16<MOM, false, GT>((int)groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+        launch_bf16<MOM, false, false, GT>(shape.groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     return check_launch(name);
 }
 

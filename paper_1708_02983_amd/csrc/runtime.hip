@@ -37,6 +37,30 @@ Options &options()
     return o;
 }
 
+UpdateShape update_shape(size_t N, bool wide)
+{
+    const Options &opt = options();
+    const size_t n4 = N / 4, cus = (size_t)num_cus();
+    long g = opt.update_groups;
+    if (g == 0) g = wide ? 8 : 4;
+    // fewer groups per thread for small N, so that the grid still covers the chip several times
+    while (g > 1 && n4 / ((size_t)g * 256) < 4 * cus) g /= 2;
+    const long layout = opt.update_layout;
+    UpdateShape sh;
+    sh.groups = (int)g;
+    sh.dies = layout == 1 || (layout == 2 && g >= 4);
+    const size_t super = (size_t)8 * g * 256;
+    sh.blocks = sh.dies ? 8 * ((n4 + super - 1) / super) : (n4 + (size_t)g * 256 - 1) / ((size_t)g * 256);
+    if (sh.blocks == 0) sh.blocks = sh.dies ? 8 : 1;
+    if (opt.update_blocks_per_cu > 0) {
+        // a persistent grid; a multiple of 8 blocks, so that a block stays on the same die for all its tiles
+        const size_t persistent = ((size_t)opt.update_blocks_per_cu * cus + 7) / 8 * 8;
+        if (sh.blocks > persistent) sh.blocks = persistent;
+    }
+    if (sh.blocks > 0x7ffffff8u) sh.blocks = 0x7ffffff8u;    // the kernels' grid-stride loops cover the rest
+    return sh;
+}
+
 std::atomic<unsigned long long> &launch_counter()
 {
     static std::atomic<unsigned long long> n{0};
@@ -49,7 +73,7 @@ extern "C" {
 
 const char *easgd_last_error(void) { return easgd::g_err; }
 
-int easgd_version(void) { return 410; }
+int easgd_version(void) { return 420; }
 
 unsigned long long easgd_launch_count(void) { return easgd::launch_counter().load(std::memory_order_relaxed); }
 
@@ -66,7 +90,8 @@ int easgd_set_option(int option, long value)
         o.update_nontemporal = value;
         return EASGD_OK;
     case EASGD_OPT_UPDATE_GROUPS:
-        if (value != 1 && value != 2 && value != 4) return easgd::fail(EASGD_EINVAL, "groups must be 1, 2 or 4, got %ld", value);
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+            return easgd::fail(EASGD_EINVAL, "groups must be 0 (chosen per call), 1, 2, 4 or 8, got %ld", value);
         o.update_groups = value;
         return EASGD_OK;
     case EASGD_OPT_GEMM_TILE:
@@ -89,6 +114,10 @@ int easgd_set_option(int option, long value)
         if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "mlp head must be 0 or 1, got %ld", value);
         o.mlp_head = value;
         return EASGD_OK;
+    case EASGD_OPT_UPDATE_LAYOUT:
+        if (value < 0 || value > 2) return easgd::fail(EASGD_EINVAL, "update layout must be 0, 1 or 2, got %ld", value);
+        o.update_layout = value;
+        return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
     }
@@ -106,6 +135,7 @@ long easgd_get_option(int option)
     case EASGD_OPT_GEMM_XCD: return o.gemm_xcd;
     case EASGD_OPT_GEMM_PAIR: return o.gemm_pair;
     case EASGD_OPT_MLP_HEAD: return o.mlp_head;
+    case EASGD_OPT_UPDATE_LAYOUT: return o.update_layout;
     default: return -1;
     }
 }

@@ -8,15 +8,35 @@ HUNDRED_ROUND_TOL = 1e-4  # after 100 free-running rounds
 
 def normwise(x: np.ndarray, y: np.ndarray) -> float:
     """max_j |x_j - y_j| / max_j |y_j| over the finite entries of the reference y
-    (NaN padding must be NaN in both)."""
-    x = np.asarray(x, dtype=np.float64)
-    y = np.asarray(y, dtype=np.float64)
-    pad = np.isnan(y)
-    assert np.array_equal(np.isnan(x), pad), "padding / validity pattern differs"
-    if pad.all():
+    (NaN padding must be NaN in both).  Evaluated in double, chunk by chunk on a few threads: the
+    full-size tensors hold hundreds of millions of entries."""
+    from concurrent.futures import ThreadPoolExecutor
+    x = np.ascontiguousarray(x).reshape(-1)
+    y = np.ascontiguousarray(y).reshape(-1)
+    assert x.shape == y.shape, "shapes differ"
+    chunk = 1 << 22
+
+    def part(s):
+        xc = x[s:s + chunk].astype(np.float64)
+        yc = y[s:s + chunk].astype(np.float64)
+        pad = np.isnan(yc)
+        same = np.array_equal(np.isnan(xc), pad)
+        if pad.any():
+            xc[pad] = 0.0
+            yc[pad] = 0.0
+        return same, bool(pad.all()), float(np.abs(yc).max()), float(np.abs(xc - yc).max())
+
+    starts = range(0, x.size, chunk)
+    if x.size > 4 * chunk:
+        with ThreadPoolExecutor(8) as ex:
+            parts = list(ex.map(part, starts))
+    else:
+        parts = [part(s) for s in starts]
+    assert all(p[0] for p in parts), "padding / validity pattern differs"
+    if all(p[1] for p in parts):
         return 0.0
-    scale = np.abs(y[~pad]).max()
-    diff = np.abs(x[~pad] - y[~pad]).max()
+    scale = max(p[2] for p in parts)
+    diff = max(p[3] for p in parts)
     return float(diff / scale) if scale > 0 else float(diff)
 
 

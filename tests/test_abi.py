@@ -139,8 +139,11 @@ def test_options_roundtrip(lib):
     lib.easgd_set_option.argtypes = [ctypes.c_int, ctypes.c_long]
     lib.easgd_get_option.restype = ctypes.c_long
     old = lib.easgd_get_option(3)
+    assert old == 0
     assert lib.easgd_set_option(3, 2) == 0 and lib.easgd_get_option(3) == 2
-    assert lib.easgd_set_option(3, 5) == -1
+    assert lib.easgd_set_option(3, 8) == 0 and lib.easgd_set_option(3, 5) == -1 and lib.easgd_get_option(3) == 8
+    assert lib.easgd_get_option(9) == 2 and lib.easgd_set_option(9, 3) == -1
+    assert lib.easgd_set_option(9, 0) == 0 and lib.easgd_get_option(9) == 0 and lib.easgd_set_option(9, 2) == 0
     assert lib.easgd_set_option(99, 1) == -1
     assert lib.easgd_set_option(3, old) == 0
     assert lib.easgd_get_option(5) == 1 and lib.easgd_set_option(5, 4) == -1

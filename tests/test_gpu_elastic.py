@@ -118,18 +118,21 @@ def test_bitwise_reproducible_and_independent_of_launch_shape(hip):
     G = workloads.update_gradients(P, N, 0, ld, seed=14)
     V = workloads.update_gradients(P, N, 1, ld, seed=14)
     results = []
-    saved = [hip.get_option(o) for o in (1, 2, 3)]
+    saved = [hip.get_option(o) for o in (1, 2, 3, 9)]
     try:
-        for blocks_per_cu, nt, groups in [(0, 1, 4), (0, 1, 4), (4, 0, 2), (1, 1, 1), (8, 0, 4)]:
+        for blocks_per_cu, nt, groups, layout in [(0, 1, 0, 2), (0, 1, 0, 2), (4, 0, 2, 0), (1, 1, 1, 0), (8, 0, 4, 0),
+                                                  (0, 1, 4, 1), (0, 0, 8, 1), (2, 1, 8, 1), (3, 0, 1, 1), (0, 1, 2, 1),
+                                                  (0, 1, 8, 0)]:
             hip.set_option(hip.OPT_UPDATE_BLOCKS_PER_CU, blocks_per_cu)
             hip.set_option(hip.OPT_UPDATE_NONTEMPORAL, nt)
             hip.set_option(hip.OPT_UPDATE_GROUPS, groups)
+            hip.set_option(hip.OPT_UPDATE_LAYOUT, layout)
             dW, dG, dWc, dV = to_dev(W), to_dev(G), to_dev(Wc), to_dev(V)
             hip.easgd_sync_round(dW, dG, dWc, 0.01, 0.1, N=N)
             hip.measgd_round(dW, dV, dG, dWc, 0.01, 0.1, 0.9, N=N)
             results.append((to_host(dW), to_host(dV), to_host(dWc)))
     finally:
-        for o, v in zip((1, 2, 3), saved):
+        for o, v in zip((1, 2, 3, 9), saved):
             hip.set_option(o, v)
     for r in results[1:]:
         for a, b in zip(results[0], r):

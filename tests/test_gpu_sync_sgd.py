@@ -94,11 +94,12 @@ def test_results_do_not_depend_on_launch_shape_options(hip):
     W, _ = workloads.update_state(P, N, ld, seed=44)
     G = workloads.update_gradients(P, N, 0, ld, seed=44)
     ref = None
-    old = (hip.get_option(hip.OPT_UPDATE_GROUPS), hip.get_option(hip.OPT_UPDATE_NONTEMPORAL))
+    old = (hip.get_option(hip.OPT_UPDATE_GROUPS), hip.get_option(hip.OPT_UPDATE_NONTEMPORAL), hip.get_option(hip.OPT_UPDATE_LAYOUT))
     try:
-        for groups in (1, 2, 4):
+        for groups, layout in ((0, 2), (1, 0), (2, 0), (4, 0), (8, 0), (1, 1), (2, 1), (4, 1), (8, 1)):
             for nt in (0, 1):
                 hip.set_option(hip.OPT_UPDATE_GROUPS, groups); hip.set_option(hip.OPT_UPDATE_NONTEMPORAL, nt)
+                hip.set_option(hip.OPT_UPDATE_LAYOUT, layout)
                 dW = to_dev(W)
                 hip.sync_sgd_round(dW, to_dev(G), float(ETA), N=N)
                 out = to_host(dW)
@@ -108,6 +109,7 @@ def test_results_do_not_depend_on_launch_shape_options(hip):
                     np.testing.assert_array_equal(out, ref)
     finally:
         hip.set_option(hip.OPT_UPDATE_GROUPS, old[0]); hip.set_option(hip.OPT_UPDATE_NONTEMPORAL, old[1])
+        hip.set_option(hip.OPT_UPDATE_LAYOUT, old[2])
 
 
 def test_full_size_on_sampled_columns(hip):

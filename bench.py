@@ -450,11 +450,11 @@ def update_roofline(hip, wl, rule, update_ms, ceilings):
     """HBM roofline of one streaming update launch at the workload's size."""
     P, N = wl.P, wl.N
     if rule == "sync_sgd":
-        return hbm_roofline(hip, "sync_sgd_vec4_kernel", ("sync_sgd", wl.momentum, P, N), 12 * P * N, update_ms, ceilings)
+        return hbm_roofline(hip, "sync_sgd_vec4_dies_kernel", ("sync_sgd", wl.momentum, P, N), 12 * P * N, update_ms, ceilings)
     if rule == "elastic_bf16":
-        return hbm_roofline(hip, "elastic_bf16_vec4_kernel", ("elastic_bf16", wl.momentum, P, N),
+        return hbm_roofline(hip, "elastic_bf16_vec4_dies_kernel", ("elastic_bf16", wl.momentum, P, N),
                             N * ((14 if wl.momentum else 10) * P + 8), update_ms, ceilings)
-    return hbm_roofline(hip, "elastic_vec4_kernel (measgd)" if wl.momentum else "elastic_vec4_kernel (easgd)",
+    return hbm_roofline(hip, "elastic_vec4_dies_kernel (measgd)" if wl.momentum else "elastic_vec4_dies_kernel (easgd)",
                         ("elastic", wl.momentum, P, N), update_bytes(wl), update_ms, ceilings)
 
 

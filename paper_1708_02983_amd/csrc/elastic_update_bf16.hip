@@ -91,7 +91,7 @@ __device__ __forceinline__ void elastic_bf16_tile(f32x4 *__restrict__ W, u16x4 *
                 if constexpr (MOM) v[q] = lp_load<NT>(V + row + j);
             }
         }
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);     // all loads of this worker before the first use
+        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);     // loads | arithmetic | stores, as in elastic_tile
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
             const size_t j = j0 + (size_t)q * STRIDE;
@@ -105,6 +105,13 @@ __device__ __forceinline__ void elastic_bf16_tile(f32x4 *__restrict__ W, u16x4 *
                     w[q][e] = we;
                     if constexpr (MOM) v[q][e] = ve;
                 }
+            }
+        }
+        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) {
                 lp_store<NT>(W + row + j, w[q]);
                 if constexpr (MOM) lp_store<NT>(V + row + j, v[q]);
             }
@@ -119,10 +126,10 @@ __device__ __forceinline__ void elastic_bf16_tile(f32x4 *__restrict__ W, u16x4 *
 
 // The N % 4 tail rides on the last block.
 template <bool MOM, bool NT, int GROUPS, bool DIES, typename GT>
-__global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restrict__ Wp, unsigned short *__restrict__ Vp,
-                                                                const GT *__restrict__ Gp,
-                                                                float *__restrict__ Wcp, int P, size_t N, size_t ld,
-                                                                float eta, float rho, float alpha, float delta)
+__device__ __forceinline__ void elastic_bf16_vec4_body(float *__restrict__ Wp, unsigned short *__restrict__ Vp,
+                                                       const GT *__restrict__ Gp,
+                                                       float *__restrict__ Wcp, int P, size_t N, size_t ld,
+                                                       float eta, float rho, float alpha, float delta)
 {
     typedef typename Vec4<GT>::type g4;
     typedef TileMap<GROUPS, DIES> Map;
@@ -144,6 +151,25 @@ __global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restric
         scalar_param<MOM, GT>(Wp, Vp, Gp, Wcp, P, n4 * 4 + threadIdx.x, ld, eta, rho, alpha, delta);
 }
 
+template <bool MOM, bool NT, int GROUPS, typename GT>
+__global__ __launch_bounds__(256) void elastic_bf16_vec4_kernel(float *__restrict__ W, unsigned short *__restrict__ V,
+                                                                const GT *__restrict__ G, float *__restrict__ Wc,
+                                                                int P, size_t N, size_t ld,
+                                                                float eta, float rho, float alpha, float delta)
+{
+    elastic_bf16_vec4_body<MOM, NT, GROUPS, false, GT>(W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+}
+
+// die-interleaved tiles, one wavefront per SIMD (one block per compute unit), as elastic_vec4_dies_kernel
+template <bool MOM, bool NT, int GROUPS, typename GT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void elastic_bf16_vec4_dies_kernel(float *__restrict__ W, unsigned short *__restrict__ V, const GT *__restrict__ G,
+                                   float *__restrict__ Wc, int P, size_t N, size_t ld,
+                                   float eta, float rho, float alpha, float delta)
+{
+    elastic_bf16_vec4_body<MOM, NT, GROUPS, true, GT>(W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
+}
+
 // Any alignment: one thread per parameter.
 template <bool MOM, typename GT>
 __global__ __launch_bounds__(256) void elastic_bf16_scalar_kernel(float *__restrict__ W, unsigned short *__restrict__ V,
@@ -160,12 +186,18 @@ template <bool MOM, bool NT, bool DIES, typename GT>
 static void launch_bf16(int groups, dim3 grid, hipStream_t s, float *W, unsigned short *V, const GT *G,
                         float *Wc, int P, size_t N, size_t ld, float eta, float rho, float alpha, float delta)
 {
+#define EASGD_BF16(GR)                                                                                                        \
+    do {                                                                                                                      \
+        if (DIES) EASGD_LAUNCH((elastic_bf16_vec4_dies_kernel<MOM, NT, GR, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); \
+        else EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, GR, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);          \
+    } while (0)
     switch (groups) {
-    case 1: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 1, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    case 2: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 2, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    case 4: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 4, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
-    default: EASGD_LAUNCH((elastic_bf16_vec4_kernel<MOM, NT, 8, DIES, GT>), grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta); break;
+    case 1: EASGD_BF16(1); break;
+    case 2: EASGD_BF16(2); break;
+    case 4: EASGD_BF16(4); break;
+    default: EASGD_BF16(8); break;
     }
+#undef EASGD_BF16
 }
 
 inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }

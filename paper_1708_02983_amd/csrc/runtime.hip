@@ -42,7 +42,8 @@ UpdateShape update_shape(size_t N, bool wide)
     const Options &opt = options();
     const size_t n4 = N / 4, cus = (size_t)num_cus();
     long g = opt.update_groups;
-    if (g == 0) g = wide ? 8 : 4;
+    if (g == 0) g = 4;
+    (void)wide;
     // fewer groups per thread for small N, so that the grid still covers the chip several times
     while (g > 1 && n4 / ((size_t)g * 256) < 4 * cus) g /= 2;
     const long layout = opt.update_layout;

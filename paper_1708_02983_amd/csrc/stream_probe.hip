@@ -7,21 +7,53 @@ namespace easgd {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// The probes use the update kernels' die-interleaved tile map with four groups per thread (TileMap<4, true>:
+// eight consecutive blocks, one per die, interleave in 1 KiB pieces inside a super-tile), so that they measure
+// what a plain stream reaches with the same access pattern; the grid is a multiple of 8 blocks.
+typedef TileMap<4, true> ProbeMap;
+
 // dst[j] = src[j]: n4 128-bit groups, 4n bytes read + 4n bytes written
 __global__ __launch_bounds__(256) void stream_copy_kernel(f32x4 *__restrict__ dst, const f32x4 *__restrict__ src, size_t n4)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < n4; j += stride)
-        __builtin_nontemporal_store(__builtin_nontemporal_load(src + j), dst + j);
+    for (size_t t = blockIdx.x; t < ProbeMap::tiles(n4); t += gridDim.x) {
+        const size_t j0 = ProbeMap::first(t, threadIdx.x);
+        if (ProbeMap::last(t) < n4) {
+            f32x4 x[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) x[q] = __builtin_nontemporal_load(src + j0 + q * ProbeMap::STRIDE);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) __builtin_nontemporal_store(x[q], dst + j0 + q * ProbeMap::STRIDE);
+        } else {
+            for (int q = 0; q < 4; ++q) {
+                const size_t j = j0 + q * ProbeMap::STRIDE;
+                if (j < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(src + j), dst + j);
+            }
+        }
+    }
 }
 
 // a[j] = b[j] + s*c[j]: two reads and one write per element, the mix of the EASGD update
 __global__ __launch_bounds__(256) void stream_triad_kernel(f32x4 *__restrict__ a, const f32x4 *__restrict__ b,
                                                            const f32x4 *__restrict__ c, float s, size_t n4)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < n4; j += stride)
-        __builtin_nontemporal_store(__builtin_nontemporal_load(b + j) + s * __builtin_nontemporal_load(c + j), a + j);
+    for (size_t t = blockIdx.x; t < ProbeMap::tiles(n4); t += gridDim.x) {
+        const size_t j0 = ProbeMap::first(t, threadIdx.x);
+        if (ProbeMap::last(t) < n4) {
+            f32x4 x[4], y[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                x[q] = __builtin_nontemporal_load(b + j0 + q * ProbeMap::STRIDE);
+                y[q] = __builtin_nontemporal_load(c + j0 + q * ProbeMap::STRIDE);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) __builtin_nontemporal_store(x[q] + s * y[q], a + j0 + q * ProbeMap::STRIDE);
+        } else {
+            for (int q = 0; q < 4; ++q) {
+                const size_t j = j0 + q * ProbeMap::STRIDE;
+                if (j < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(b + j) + s * __builtin_nontemporal_load(c + j), a + j);
+            }
+        }
+    }
 }
 
 // a[j] = c[j] + s*d[j], b[j] = d[j] + s*e[j]: three reads and two writes per element, the mix of the momentum update
@@ -29,19 +61,39 @@ __global__ __launch_bounds__(256) void stream_mix32_kernel(f32x4 *__restrict__ a
                                                            const f32x4 *__restrict__ c, const f32x4 *__restrict__ d,
                                                            const f32x4 *__restrict__ e, float s, size_t n4)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < n4; j += stride) {
-        const f32x4 x = __builtin_nontemporal_load(c + j), y = __builtin_nontemporal_load(d + j),
-                    z = __builtin_nontemporal_load(e + j);
-        __builtin_nontemporal_store(x + s * y, a + j);
-        __builtin_nontemporal_store(y + s * z, b + j);
+    for (size_t t = blockIdx.x; t < ProbeMap::tiles(n4); t += gridDim.x) {
+        const size_t j0 = ProbeMap::first(t, threadIdx.x);
+        if (ProbeMap::last(t) < n4) {
+            f32x4 x[4], y[4], z[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                x[q] = __builtin_nontemporal_load(c + j0 + q * ProbeMap::STRIDE);
+                y[q] = __builtin_nontemporal_load(d + j0 + q * ProbeMap::STRIDE);
+                z[q] = __builtin_nontemporal_load(e + j0 + q * ProbeMap::STRIDE);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                __builtin_nontemporal_store(x[q] + s * y[q], a + j0 + q * ProbeMap::STRIDE);
+                __builtin_nontemporal_store(y[q] + s * z[q], b + j0 + q * ProbeMap::STRIDE);
+            }
+        } else {
+            for (int q = 0; q < 4; ++q) {
+                const size_t j = j0 + q * ProbeMap::STRIDE;
+                if (j < n4) {
+                    const f32x4 x = __builtin_nontemporal_load(c + j), y = __builtin_nontemporal_load(d + j),
+                                z = __builtin_nontemporal_load(e + j);
+                    __builtin_nontemporal_store(x + s * y, a + j);
+                    __builtin_nontemporal_store(y + s * z, b + j);
+                }
+            }
+        }
     }
 }
 
 static int probe_grid(size_t n4, dim3 &grid)
 {
-    size_t blocks = (n4 + 255) / 256;
-    if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;
+    size_t blocks = ProbeMap::tiles(n4);
+    if (blocks > 0x7ffffff8u) blocks = 0x7ffffff8u;     // a multiple of 8; the kernels' loops cover the rest
     grid = dim3((unsigned)blocks);
     return 0;
 }

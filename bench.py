@@ -550,6 +550,11 @@ def main():
     ap.add_argument("--mlp-head", type=int, default=None, choices=(0, 1),
                     help="library option EASGD_OPT_MLP_HEAD: 0 = the last layer as three launches, default: the "
                          "library's (one launch for a narrow last layer)")
+    ap.add_argument("--update-layout", type=int, default=None, choices=(0, 1, 2),
+                    help="library option EASGD_OPT_UPDATE_LAYOUT of the streaming update kernels: 0 = contiguous tiles, "
+                         "1 = die-interleaved, default: the library's (chosen per call)")
+    ap.add_argument("--update-groups", type=int, default=None, choices=(0, 1, 2, 4, 8),
+                    help="library option EASGD_OPT_UPDATE_GROUPS, default: the library's (chosen per call)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P replicas live in one HBM); --gpus must be 1. "
@@ -569,6 +574,10 @@ def main():
         hip.set_option(hip.OPT_GEMM_XCD, args.gemm_xcd)
     if args.mlp_head is not None:
         hip.set_option(hip.OPT_MLP_HEAD, args.mlp_head)
+    if args.update_layout is not None:
+        hip.set_option(hip.OPT_UPDATE_LAYOUT, args.update_layout)
+    if args.update_groups is not None:
+        hip.set_option(hip.OPT_UPDATE_GROUPS, args.update_groups)
     wl = workloads.WORKLOADS[args.workload]
     steps = args.steps if args.steps is not None else (300 if wl.has_grad else 100)
     warmup = args.warmup if args.warmup is not None else (20 if wl.has_grad else 5)

@@ -545,7 +545,7 @@ def main():
     ap.add_argument("--gemm-pair", type=int, default=None, choices=(0, 1),
                     help="library option EASGD_OPT_GEMM_PAIR: 0 = one launch per matrix product (tells the products "
                          "apart in a profile), default: the library's (shared launches)")
-    ap.add_argument("--gemm-xcd", type=int, default=None, choices=(0, 1, 2),
+    ap.add_argument("--gemm-xcd", type=int, default=None, choices=(0, 1, 2, 3),
                     help="library option EASGD_OPT_GEMM_XCD (block order of the matrix products), default: the library's")
     ap.add_argument("--mlp-head", type=int, default=None, choices=(0, 1),
                     help="library option EASGD_OPT_MLP_HEAD: 0 = the last layer as three launches, default: the "

@@ -324,8 +324,10 @@ typedef enum {
                                             (below which ordering two streams costs more than it hides), else 0 */
     EASGD_OPT_GEMM_XCD             = 6,  /* 1 = the blocks of a matrix product are renumbered so that each of the eight dies
                                             works on whole workers, and in products that apply the worker rule a die walks
-                                            its workers tile by tile, so that it fetches each tile of the center once
-                                            (default); 2 = the same without that interleaving; 0 = plain block order */
+                                            its workers tile by tile, so that it fetches each tile of the center once, going
+                                            through the result in bands of up to eight tile columns, so that the tiles it
+                                            works on at one time share their operand panels (default); 3 = the same walk in
+                                            row-major tile order; 2 = whole workers per die only; 0 = plain block order */
     EASGD_OPT_GEMM_PAIR            = 7,  /* 1 = independent products of backward propagation share a launch where their tile
                                             shapes allow (default), 0 = one launch per product */
     EASGD_OPT_MLP_HEAD             = 8,  /* 1 = a last layer of at most 16 classes takes one launch for its forward product, the

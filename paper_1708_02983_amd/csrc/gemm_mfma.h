@@ -54,9 +54,12 @@ struct GemmArgs {
     int xcd_chunk;                      // 0 = plain block order; else grid/8 (see the kernel)
     int die_workers;                    // > 0 (needs xcd_chunk > 0, splits == 1, P == 8 * die_workers): a die walks its
                                         // workers' tiles tile by tile, the workers of a tile next to each other
-    // ceil(2^32 / d) for the three divisors of the block -> tile mapping (tiles per worker, tiles_n, die_workers),
+    int band_log2;                      // > 0 (needs die_workers > 0, tiles_n a multiple of 2^band_log2): that walk goes
+                                        // through C in bands of 2^band_log2 tile columns, down each band row by row
+    int band_tiles;                     // tiles_m << band_log2
+    // ceil(2^32 / d) for the divisors of the block -> tile mapping (tiles per worker, tiles_n, die_workers, band_tiles),
     // or 0 where the host could not guarantee that the product form is exact (then the kernel divides)
-    unsigned magic_tiles, magic_tiles_n, magic_die;
+    unsigned magic_tiles, magic_tiles_n, magic_die, magic_band;
     // elastic epilogues: replica / momentum tiles indexed like C (worker stride c_ws, row stride ldc);
     // the center has the row stride ldc and no worker stride
     float *Wt, *Vt;
@@ -158,8 +161,22 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
             w = rest / p.splits;
         }
     }
-    const int tile_m = fast_div(tile, p.tiles_n, p.magic_tiles_n);
-    const int m0 = tile_m * BM, n0 = (tile - tile_m * p.tiles_n) * BN;
+    int tile_m, tile_n;
+    if (p.band_log2 > 0) {
+        // The blocks a die runs at the same time are a few dozen consecutive tiles of each of its workers.  In
+        // row-major tile order those are one row of tiles: one panel of A and every panel of B, so B is swept
+        // again for each row of tiles, and what streams through the L2 in between (the replica and momentum
+        // tiles of the epilogue) has evicted it by then.  Walking bands of 2^band_log2 tile columns row by row
+        // makes the concurrent tiles a near-square patch that shares a few panels of each operand.
+        const int band = fast_div(tile, p.band_tiles, p.magic_band);
+        const int rem = tile - band * p.band_tiles;
+        tile_m = rem >> p.band_log2;
+        tile_n = (band << p.band_log2) + (rem & ((1 << p.band_log2) - 1));
+    } else {
+        tile_m = fast_div(tile, p.tiles_n, p.magic_tiles_n);
+        tile_n = tile - tile_m * p.tiles_n;
+    }
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int k_begin = split * p.k_per_split;
     const int k_end = min(p.K, k_begin + p.k_per_split);
 

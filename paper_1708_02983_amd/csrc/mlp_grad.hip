@@ -379,11 +379,20 @@ static unsigned place_blocks(GemmArgs &a)
     size_t total = (size_t)a.tiles_m * a.tiles_n * a.splits * a.P;
     a.xcd_chunk = 0;
     a.die_workers = 0;
+    a.band_log2 = 0;
+    a.band_tiles = 0;
     if (options().gemm_xcd && total >= 64) {
         total = (total + 7) / 8 * 8;
         a.xcd_chunk = (int)(total / 8);
         // a product with an elastic epilogue (it has a center): interleave the workers of a die
-        if (a.center && a.splits == 1 && a.P % 8 == 0 && options().gemm_xcd == 1) a.die_workers = a.P / 8;
+        const long order = options().gemm_xcd;
+        if (a.center && a.splits == 1 && a.P % 8 == 0 && (order == 1 || order == 3)) {
+            a.die_workers = a.P / 8;
+            // bands of 8 (4, 2) tile columns when the tile columns divide into them
+            if (order == 1 && a.tiles_m > 1)
+                a.band_log2 = a.tiles_n % 8 == 0 ? 3 : a.tiles_n % 4 == 0 ? 2 : a.tiles_n % 2 == 0 ? 1 : 0;
+            a.band_tiles = a.tiles_m << a.band_log2;
+        }
     }
     // the kernel's divisions by multiplication: exact while dividend * divisor < 2^32
     auto magic = [&](size_t dividend_max, int d) -> unsigned {
@@ -394,6 +403,7 @@ static unsigned place_blocks(GemmArgs &a)
     a.magic_tiles = magic(total, (int)tiles);
     a.magic_tiles_n = magic(tiles, a.tiles_n);
     a.magic_die = magic(total / 8 + 1, a.die_workers);
+    a.magic_band = magic(tiles, a.band_tiles);
     return (unsigned)total;
 }
 

@@ -104,7 +104,7 @@ int easgd_set_option(int option, long value)
         o.round_overlap = value;
         return EASGD_OK;
     case EASGD_OPT_GEMM_XCD:
-        if (value < 0 || value > 2) return easgd::fail(EASGD_EINVAL, "gemm xcd must be 0, 1 or 2, got %ld", value);
+        if (value < 0 || value > 3) return easgd::fail(EASGD_EINVAL, "gemm xcd must be in [0,3], got %ld", value);
         o.gemm_xcd = value;
         return EASGD_OK;
     case EASGD_OPT_GEMM_PAIR:

@@ -148,7 +148,7 @@ def test_options_roundtrip(lib):
     assert lib.easgd_set_option(3, old) == 0
     assert lib.easgd_get_option(5) == 1 and lib.easgd_set_option(5, 4) == -1
     assert lib.easgd_set_option(5, 2) == 0 and lib.easgd_get_option(5) == 2 and lib.easgd_set_option(5, 1) == 0
-    assert lib.easgd_get_option(6) == 1 and lib.easgd_set_option(6, 3) == -1
+    assert lib.easgd_get_option(6) == 1 and lib.easgd_set_option(6, 4) == -1 and lib.easgd_set_option(6, 3) == 0 and lib.easgd_set_option(6, 1) == 0
     assert lib.easgd_set_option(6, 0) == 0 and lib.easgd_get_option(6) == 0 and lib.easgd_set_option(6, 1) == 0
     assert lib.easgd_get_option(4) == 0 and lib.easgd_set_option(4, 4) == -1
     assert lib.easgd_get_option(7) == 1 and lib.easgd_set_option(7, 2) == -1 and lib.easgd_set_option(7, 1) == 0

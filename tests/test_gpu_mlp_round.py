@@ -266,19 +266,21 @@ def test_local_steps_between_exchanges(hip, momentum):
             oV[:, :N] = to_host(dV)[:, :N]
 
 
-@pytest.mark.parametrize("dims,P,b", [((200, 264, 136, 10), 8, 100), ((512, 384, 10), 40, 128), ((300, 260, 10), 16, 64)],
+@pytest.mark.parametrize("dims,P,b", [((200, 264, 136, 10), 8, 100), ((512, 384, 10), 40, 128), ((300, 260, 10), 16, 64),
+                                      ((200, 512, 256, 10), 8, 36)],
                          ids=lambda v: str(v).replace(" ", ""))
 def test_block_order_changes_nothing(hip, dims, P, b):
     """EASGD_OPT_GEMM_XCD only renumbers the blocks of a product (plain order; whole workers per die; a die's workers
-    interleaved tile by tile in the products that apply the worker rule): every block computes the same tile the
-    same way, so rounds and gradients are the same bits under all three orders (P a multiple of 8 makes the third
-    order differ from the second)."""
+    interleaved tile by tile in the products that apply the worker rule, in bands of tile columns or in row-major
+    tile order): every block computes the same tile the same way, so rounds and gradients are the same bits under
+    all four orders (P a multiple of 8 makes the interleaved orders differ from the second; at 64-wide tiles the
+    widths 512, 256 and 384 give bands of 8, 4 and 2 tile columns, the others none)."""
     N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=37)
     dX, dy = to_dev(X), to_dev(y)
     old = hip.get_option(hip.OPT_GEMM_XCD)
     out = []
     try:
-        for order in (0, 1, 2):
+        for order in (0, 1, 2, 3):
             hip.set_option(hip.OPT_GEMM_XCD, order)
             res = []
             for momentum in (False, True):

@@ -491,6 +491,19 @@ def training_report(hip, wl, steps, warmup, name, full):
     out["update_in_round"] = {"GBs_algorithmic": round(update_bytes(wl) / (r["update_ms"] * 1e-3) / 1e9, 1),
                               "note": "elastic update of the two-call path; replicas of this size are served partly "
                                       "from the 256 MB last-level cache, so this is not an HBM figure"}
+    if len(wl.dims) == 2 and hip.get_option(hip.OPT_ROUND_SINGLE_LAUNCH) == 0:
+        # a single-layer network: the same round as ONE launch (both phases in one grid, a barrier over the grid
+        # between them) instead of two dependent launches; opt-in in the library, timed here for comparison
+        hip.set_option(hip.OPT_ROUND_SINGLE_LAUNCH, 1)
+        try:
+            s1 = bench_training(hip, wl, steps, warmup, one_call=True)
+        finally:
+            hip.set_option(hip.OPT_ROUND_SINGLE_LAUNCH, 0)
+        out["single_launch_round"] = {
+            "rounds_per_s": round(steps / s1["elapsed_s"], 2), "ms_per_step": round(s1["ms_per_step"], 4),
+            "launches_per_round": s1["launches_per_round"],
+            "note": "EASGD_OPT_ROUND_SINGLE_LAUNCH = 1 (not the default): forward and softmax, grid-wide barrier, "
+                    "gradient and update in one launch"}
     if wl.momentum:
         # an extension (the paper names low precision only as future work): the same rounds with the momentum
         # buffers stored as bfloat16

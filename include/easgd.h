@@ -254,6 +254,19 @@ int easgd_grad_bf16(const int *dims, int n_layers,
  * their record/wait pair.  A caller that wants to capture the call in a HIP graph makes one eager
  * call with the same shape first, so that the stream is not created under capture (or sets
  * EASGD_OPT_ROUND_OVERLAP to 0 or 3, which keep the call on the caller's stream).
+ *
+ * With EASGD_OPT_ROUND_SINGLE_LAUNCH set to 1 (default 0) a single-layer network (softmax regression) of at
+ * most 16 classes with b <= 256 and P*b <= 2048 takes ONE launch for the whole call (the gradient entry
+ * points take the same launch without the update): forward propagation and softmax, a
+ * barrier over the grid, then gradient, worker rule and center rule per parameter with the workers in
+ * ascending order.  The gradient's sum over the minibatch has another (fixed) order there than in the
+ * matrix-product kernels, so results agree with the separate launches to rounding, not bit for bit.
+ * The barrier is a count of arrivals in device memory that belongs to the library, one per (device,
+ * stream) that has taken this path, at most 64 streams per device; a call on a stream under capture, or
+ * on a 65th stream, takes the separate launches instead.  All blocks of the grid are resident at once,
+ * so the wait ends; it is bounded all the same (EASGD_OPT_ROUND_SPIN_LIMIT): a block that gives up
+ * writes NaN into its share of W, Wc, G and loss instead of a result, and easgd_round_barrier_timeouts
+ * counts it.
  * Errors: as easgd_grad.
  */
 size_t easgd_mlp_round_workspace_bytes(const int *dims, int n_layers, int P, int b);
@@ -333,10 +346,18 @@ typedef enum {
     EASGD_OPT_MLP_HEAD             = 8,  /* 1 = a last layer of at most 16 classes takes one launch for its forward product, the
                                             softmax cross-entropy and its input-gradient product (default), 0 = three launches
                                             (split-K product, softmax, product) */
-    EASGD_OPT_UPDATE_LAYOUT        = 9   /* which parameters a block of the streaming update kernels owns: 0 = a contiguous run of
+    EASGD_OPT_UPDATE_LAYOUT        = 9,  /* which parameters a block of the streaming update kernels owns: 0 = a contiguous run of
                                             groups*1024 parameters; 1 = eight consecutive blocks (one per die) interleave in pieces
                                             of 1 KiB inside a super-tile, so that every die's requests spread over all memory
                                             channels; 2 = chosen per call (default): 1 when N is large enough for 4 groups */
+    EASGD_OPT_ROUND_SINGLE_LAUNCH  = 10, /* 1 = easgd_grad, easgd_grad_static, easgd_grad_bf16, easgd_mlp_round and
+                                            easgd_mlp_round_bf16v take ONE launch for a single-layer network of at most 16
+                                            classes with b <= 256 and P*b <= 2048 (both phases of the round in one grid with
+                                            a grid-wide barrier between; see easgd_mlp_round); 0 = separate launches
+                                            (default: measured on MI355X the barrier over the eight dies costs what the
+                                            launch boundary it replaces costs) */
+    EASGD_OPT_ROUND_SPIN_LIMIT     = 11  /* polls after which a block of that launch gives up waiting at the barrier;
+                                            0 = 2^22 (default; some seconds) */
 } easgd_option;
 
 int easgd_set_option(int option, long value);
@@ -356,6 +377,11 @@ int easgd_stream_triad(float *a, const float *b, const float *c, size_t n, float
 /*   easgd_stream_mix32  a[j] = c[j] + s*d[j], b[j] = d[j] + s*e[j]   reads 12n bytes, writes 8n bytes
  *                       (three reads and two writes per element: the mix of the momentum update) */
 int easgd_stream_mix32(float *a, float *b, const float *c, const float *d, const float *e, size_t n, float s, void *stream);
+
+/* Number of blocks that ever gave up waiting at the barrier of a single-launch round on `stream` of the
+ * current device (0 unless something kept part of a grid from running for seconds).  Synchronises `stream`.
+ * Returns the count, or a negative easgd_status. */
+long easgd_round_barrier_timeouts(void *stream);
 
 /* Measurement aid: number of kernel launches the library has issued in this process so far
  * (the difference across a call is the number of launches of that call). */

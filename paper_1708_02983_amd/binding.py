@@ -27,6 +27,8 @@ OPT_GEMM_XCD = 6
 OPT_GEMM_PAIR = 7
 OPT_MLP_HEAD = 8
 OPT_UPDATE_LAYOUT = 9
+OPT_ROUND_SINGLE_LAUNCH = 10
+OPT_ROUND_SPIN_LIMIT = 11
 
 
 class EasgdError(RuntimeError):
@@ -79,6 +81,8 @@ def _load() -> ctypes.CDLL:
     lib.easgd_stream_triad.restype = i
     lib.easgd_stream_mix32.argtypes = [vp, vp, vp, vp, vp, sz, f, vp]
     lib.easgd_stream_mix32.restype = i
+    lib.easgd_round_barrier_timeouts.argtypes = [vp]
+    lib.easgd_round_barrier_timeouts.restype = ctypes.c_long
     lib.easgd_launch_count.argtypes = []
     lib.easgd_launch_count.restype = ctypes.c_ulonglong
     lib.easgd_set_option.argtypes = [i, ctypes.c_long]
@@ -325,6 +329,14 @@ def stream_mix32(a, b, c, d, e, s: float, stream=None) -> None:
     _check(_lib.easgd_stream_mix32(_dev("a", a, torch.float32, n), _dev("b", b, torch.float32, n),
                                    _dev("c", c, torch.float32, n), _dev("d", d, torch.float32, n),
                                    _dev("e", e, torch.float32, n), n, s, _stream(stream)))
+
+
+def round_barrier_timeouts(stream=None) -> int:
+    """Blocks that ever gave up waiting at the barrier of a single-launch round on `stream` (synchronises it)."""
+    n = int(_lib.easgd_round_barrier_timeouts(_stream(stream)))
+    if n < 0:
+        _check(n)
+    return n
 
 
 def launch_count() -> int:

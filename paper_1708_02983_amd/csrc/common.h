@@ -31,6 +31,8 @@ struct Options {
     std::atomic<long> gemm_xcd{1};
     std::atomic<long> gemm_pair{1};
     std::atomic<long> mlp_head{1};
+    std::atomic<long> round_single_launch{0};
+    std::atomic<long> round_spin_limit{0};
 };
 Options &options();
 

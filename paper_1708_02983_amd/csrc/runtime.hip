@@ -74,7 +74,7 @@ extern "C" {
 
 const char *easgd_last_error(void) { return easgd::g_err; }
 
-int easgd_version(void) { return 420; }
+int easgd_version(void) { return 430; }
 
 unsigned long long easgd_launch_count(void) { return easgd::launch_counter().load(std::memory_order_relaxed); }
 
@@ -119,6 +119,14 @@ int easgd_set_option(int option, long value)
         if (value < 0 || value > 2) return easgd::fail(EASGD_EINVAL, "update layout must be 0, 1 or 2, got %ld", value);
         o.update_layout = value;
         return EASGD_OK;
+    case EASGD_OPT_ROUND_SINGLE_LAUNCH:
+        if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "round single launch must be 0 or 1, got %ld", value);
+        o.round_single_launch = value;
+        return EASGD_OK;
+    case EASGD_OPT_ROUND_SPIN_LIMIT:
+        if (value < 0 || value > 0x7fffffffL) return easgd::fail(EASGD_EINVAL, "round spin limit must be in [0, 2^31), got %ld", value);
+        o.round_spin_limit = value;
+        return EASGD_OK;
     default:
         return easgd::fail(EASGD_EINVAL, "unknown option %d", option);
     }
@@ -137,6 +145,8 @@ long easgd_get_option(int option)
     case EASGD_OPT_GEMM_PAIR: return o.gemm_pair;
     case EASGD_OPT_MLP_HEAD: return o.mlp_head;
     case EASGD_OPT_UPDATE_LAYOUT: return o.update_layout;
+    case EASGD_OPT_ROUND_SINGLE_LAUNCH: return o.round_single_launch;
+    case EASGD_OPT_ROUND_SPIN_LIMIT: return o.round_spin_limit;
     default: return -1;
     }
 }

@@ -128,3 +128,45 @@ void oracle_sync_sgd_round(float *W, float *V, const float *G,
         }
     }
 }
+
+/*
+ * The master interacting with ONE worker at a time (Section 2.6, Algorithm 1 "Original EASGD", and Section 5.1
+ * "Async EASGD" / "Async MEASGD").  For the worker j whose turn it is, the loop body of Algorithm 1 does, with the
+ * weights W^j and the center Wc as they are when the turn starts:
+ *     worker:  W^j  <- W^j - eta * ( dW^j + rho * (W^j - Wc) )                 Eq. (1)
+ *              (with momentum, Eq. (5),(6):  V^j <- mu V^j - eta dW^j ;  W^j <- W^j + V^j - eta rho (W^j - Wc))
+ *     master:  Wc   <- Wc + eta * rho * (W^j - Wc)                              the one-worker form of Eq. (2)
+ * Both right-hand sides use the values from the start of the turn (the master fetches W^j before the worker
+ * updates it).  Original EASGD takes the turns in rank order (j = t mod P), Async EASGD in the order in which the
+ * workers arrive (first come, first served); either way the master serves one worker at a time, so a schedule
+ * is a sequence of worker indices, given here as `order[0..n_order)`.  A worker may come up more than once; its
+ * gradient row is used as it is each time.
+ *
+ * W, G (and V, or NULL for the plain rule): [P][ld], first N entries of a row valid; Wc: [N].  In place.
+ * State is fp32, every right-hand side is evaluated in double and rounded once when stored (the center is
+ * stored, i.e. rounded, after every turn: the next worker sees what is in memory).
+ */
+void oracle_async_easgd(float *W, float *V, const float *G, float *Wc,
+                        int P, size_t N, size_t ld, const int *order, int n_order,
+                        double eta, double rho, double mu, double center_coef)
+{
+    (void)P;
+    for (int t = 0; t < n_order; ++t) {
+        const int j = order[t];
+        long long p;
+#pragma omp parallel for schedule(static)
+        for (p = 0; p < (long long)N; ++p) {
+            const size_t k = (size_t)j * ld + (size_t)p;
+            const double w = (double)W[k], c = (double)Wc[p], g = (double)G[k];
+            const double diff = w - c;
+            if (V) {
+                const float v_new = (float)(mu * (double)V[k] - eta * g);           /* Eq. (5) */
+                V[k] = v_new;
+                W[k] = (float)(w + (double)v_new - eta * rho * diff);              /* Eq. (6) */
+            } else {
+                W[k] = (float)(w - eta * (g + rho * diff));                        /* Eq. (1) */
+            }
+            Wc[p] = (float)(c + center_coef * diff);                               /* Eq. (2), one worker */
+        }
+    }
+}

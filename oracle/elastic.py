@@ -44,6 +44,10 @@ def _load():
         lib.oracle_sync_sgd_round.argtypes = [f32p, f32p, f32p, ctypes.c_int, ctypes.c_size_t,
                                               ctypes.c_size_t, ctypes.c_double, ctypes.c_double]
         lib.oracle_sync_sgd_round.restype = None
+        lib.oracle_async_easgd.argtypes = [f32p, f32p, f32p, f32p, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
+                                           ctypes.POINTER(ctypes.c_int), ctypes.c_int, ctypes.c_double,
+                                           ctypes.c_double, ctypes.c_double, ctypes.c_double]
+        lib.oracle_async_easgd.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         lib.oracle_set_num_threads.restype = None
@@ -119,3 +123,27 @@ def sync_sgd_round(W: np.ndarray, G: np.ndarray, eta: float, V: Optional[np.ndar
         raise ValueError("ld < N")
     _load().oracle_sync_sgd_round(_ptr(W), None if V is None else _ptr(V), _ptr(G), P, N, ld,
                                   float(eta), float(mu))
+
+
+def async_easgd(W: np.ndarray, G: np.ndarray, Wc: np.ndarray, order, eta: float, rho: float,
+                V: Optional[np.ndarray] = None, mu: float = 0.0, N: Optional[int] = None,
+                center_coef: Optional[float] = None) -> None:
+    """The master serving one worker at a time, in the sequence ``order`` (Algorithm 1 in rank order; Async
+    EASGD / Async MEASGD in arrival order): per turn Eq. (1) (Eq. (5),(6) with V) for that worker and the
+    one-worker form of Eq. (2) for the center, both from the values at the start of the turn.  In place."""
+    _check("W", W)
+    P, ld = W.shape
+    N = Wc.shape[0] if N is None else N
+    _check("G", G, (P, ld))
+    _check("Wc", Wc, (N,))
+    if V is not None:
+        _check("V", V, (P, ld))
+    if ld < N:
+        raise ValueError("ld < N")
+    seq = np.ascontiguousarray(np.asarray(order, dtype=np.int32))
+    if seq.ndim != 1 or (seq.size and (seq.min() < 0 or seq.max() >= P)):
+        raise ValueError("order must be a sequence of worker indices in [0, P)")
+    cc = float(eta) * float(rho) if center_coef is None else float(center_coef)
+    _load().oracle_async_easgd(_ptr(W), None if V is None else _ptr(V), _ptr(G), _ptr(Wc), P, N, ld,
+                               seq.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), int(seq.size),
+                               float(eta), float(rho), float(mu), cc)

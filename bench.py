@@ -263,7 +263,9 @@ def bench_host_fed(hip, wl, steps, warmup):
 def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
     """rule = "elastic": the workload's EASGD / MEASGD update; "sync_sgd": the synchronous data-parallel SGD
     round on the same replicas and gradients (every replica moves by the gradient sum); "elastic_bf16": the
-    workload's update with gradients and momentum buffers stored as bfloat16 (an extension)."""
+    workload's update with gradients and momentum buffers stored as bfloat16 (an extension); "async": the master
+    serving the workers one at a time in rank order (Algorithm 1), one launch per sweep over the workers;
+    "hogwild": all workers exchanging with the center at once, lock-free (Hogwild EASGD)."""
     import torch
     P, N = wl.P, wl.N
     # replica rows start on 1 KiB boundaries (ld = N rounded up to 256 elements; the padding is never touched): the
@@ -278,6 +280,8 @@ def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
         Gs = [g.to(torch.bfloat16) for g in Gs]
         dV = torch.zeros((P, ld), dtype=torch.bfloat16, device="cuda") if wl.momentum else None
 
+    rank_order = list(range(P))
+
     def step(t):
         if rule == "elastic_bf16" and wl.momentum:
             hip.measgd_round_bf16(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta, N=N)
@@ -285,6 +289,10 @@ def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
             hip.easgd_sync_round_bf16(dW, Gs[t % pool], dWc, wl.eta, wl.rho, N=N)
         elif rule == "sync_sgd":
             hip.sync_sgd_round(dW, Gs[t % pool], wl.eta / P, V=dV, delta=wl.delta or 0.0, N=N)
+        elif rule == "async":
+            hip.async_easgd_round(dW, Gs[t % pool], dWc, rank_order, wl.eta, wl.rho, V=dV, delta=wl.delta or 0.0, N=N)
+        elif rule == "hogwild":
+            hip.hogwild_easgd_round(dW, Gs[t % pool], dWc, wl.eta, wl.rho, V=dV, delta=wl.delta or 0.0, N=N)
         elif wl.momentum:
             hip.measgd_round(dW, dV, Gs[t % pool], dWc, wl.eta, wl.rho, wl.delta, N=N)
         else:
@@ -455,6 +463,11 @@ def update_roofline(hip, wl, rule, update_ms, ceilings):
     if rule == "elastic_bf16":
         return hbm_roofline(hip, "elastic_bf16_vec4_dies_kernel", ("elastic_bf16", wl.momentum, P, N),
                             N * ((14 if wl.momentum else 10) * P + 8), update_ms, ceilings)
+    if rule == "async":      # P turns: W, g (V) read and W (V) written per turn, the center read and written once
+        return hbm_roofline(hip, "async_vec4_dies_kernel", ("async", wl.momentum, P, N), update_bytes(wl), update_ms, ceilings)
+    if rule == "hogwild":    # per worker: W, g read, W written, the center read and one read-modify-write added to it
+        return hbm_roofline(hip, "hogwild_vec4_kernel", ("hogwild", wl.momentum, P, N),
+                            N * P * ((32 if wl.momentum else 24)), update_ms, ceilings)
     return hbm_roofline(hip, "elastic_vec4_dies_kernel (measgd)" if wl.momentum else "elastic_vec4_dies_kernel (easgd)",
                         ("elastic", wl.momentum, P, N), update_bytes(wl), update_ms, ceilings)
 
@@ -639,6 +652,17 @@ def main():
             "rounds_per_s": round(100 / r3["elapsed_s"], 2), "ms_per_step": round(r3["ms_per_step"], 4),
             "roofline": update_roofline(hip, w4, "sync_sgd", r3["update_ms"], ceilings)}
         torch.cuda.empty_cache()
+        # the asynchronous exchanges the paper compares the synchronous round with, on cfg4's replicas: the master
+        # serving one worker at a time (one sweep over the workers in rank order per launch; deterministic), and the
+        # lock-free exchange of all workers at once (not reproducible from run to run)
+        for rule, label in (("async", "one worker at a time in rank order (Original / Async EASGD; async_easgd_round)"),
+                            ("hogwild", "all workers at once, lock-free (Hogwild EASGD; hogwild_easgd_round)")):
+            r4 = bench_update_only(hip, w4, 100, 5, rule=rule)
+            extra[rule + "_easgd_cfg4_shape"] = {
+                "workload": "P=8 replicas x 61M fp32 parameters, " + label,
+                "rounds_per_s": round(100 / r4["elapsed_s"], 2), "ms_per_step": round(r4["ms_per_step"], 4),
+                "roofline": update_roofline(hip, w4, rule, r4["update_ms"], ceilings)}
+            torch.cuda.empty_cache()
         # an extension (the paper names low precision only as future work): the same updates with gradients and
         # momentum buffers stored as bfloat16, fp32 replicas, center and arithmetic
         for name in ("cfg4", "cfg5"):

@@ -100,6 +100,41 @@ int measgd_round(float *W, float *V, const float *G, float *Wc,
                  float eta, float rho, float delta, void *stream);
 
 /*
+ * The asynchronous exchanges that the paper compares Sync EASGD with, on the same replicas (comparison points:
+ * the deterministic fused round above is the method).
+ *
+ * async_easgd_round: the master serves ONE worker at a time (Section 2.6 and Algorithm 1, "Original EASGD",
+ * in rank order; Section 5.1, "Async EASGD" / "Async MEASGD", in the order in which workers arrive).  A
+ * schedule is the sequence of workers served, order[0 .. n_order).  Per turn of worker i = order[t], from the
+ * values at the start of the turn:
+ *     d = W[i][j] - Wc[j]
+ *     W[i][j] <- W[i][j] - eta*(G[i][j] + rho*d)                       Eq. (1)
+ *       (V != NULL:  V[i][j] <- delta*V[i][j] - eta*G[i][j];  W[i][j] <- W[i][j] + V[i][j] - eta*rho*d    Eq. (5),(6))
+ *     Wc[j]   <- Wc[j] + eta*rho*d                                     Eq. (2) for one worker
+ * One launch for the whole schedule: the thread that owns parameter j takes the turns one after the other with
+ * the center in a register, so the result is that of n_order separate one-worker exchanges, bit for bit, and is
+ * reproducible.  A worker may come up more than once; its gradient row is used as it is each time.
+ *   order  HOST in [n_order]   worker indices in [0, P); copied before the call returns
+ *   0 <= n_order <= EASGD_MAX_SCHEDULE (longer schedules: several calls); P <= 256.
+ *   HBM traffic N*(12*n_order + 8) bytes (Eq. (1)), N*(20*n_order + 8) bytes (Eq. (5),(6)).
+ *
+ * hogwild_easgd_round: Section 5.1, "Hogwild EASGD" -- all P workers exchange with the center at the same time
+ * and nothing orders them: each worker reads the center as it finds it, applies Eq. (1) (Eq. (5),(6)) with that
+ * value and adds eta*rho*(W[i][j] - Wc[j]) to the center with a floating-point atomic add.  Which center value a
+ * worker sees and the order of the additions vary from run to run: W and Wc are NOT reproducible (that is what
+ * the comparison is about).  Every interleaving gives the same V, and leaves sum_i W[i][j] + Wc[j] equal to its
+ * value before the call minus eta * sum_i G[i][j] (plus sum_i V[i][j] (new) with momentum), up to rounding.
+ *   Wc must be ordinary device memory (the hardware's fp32 atomic add is used).
+ * Other arguments, alignment rule (a scalar kernel serves operands that are not 16-byte aligned) and errors as
+ * for easgd_sync_round / measgd_round.
+ */
+#define EASGD_MAX_SCHEDULE 256
+int async_easgd_round(float *W, float *V, const float *G, float *Wc, int P, size_t N, size_t ld,
+                      const int *order, int n_order, float eta, float rho, float delta, void *stream);
+int hogwild_easgd_round(float *W, float *V, const float *G, float *Wc, int P, size_t N, size_t ld,
+                        float eta, float rho, float delta, void *stream);
+
+/*
  * The two rounds above with the gradients (and the momentum buffers) STORED as bfloat16 -- an
  * extension: the paper keeps fp32 throughout and names low precision only as future work (Section 3.2).
  * Replicas and center stay fp32, all arithmetic is fp32; the HBM stream shrinks from N*(12P+8) to

@@ -56,6 +56,10 @@ def _load() -> ctypes.CDLL:
     lib.measgd_round_bf16v.restype = i
     lib.sync_sgd_round.argtypes = [vp, vp, vp, i, sz, sz, f, f, vp]
     lib.sync_sgd_round.restype = i
+    lib.async_easgd_round.argtypes = [vp, vp, vp, vp, i, sz, sz, ctypes.POINTER(ctypes.c_int), i, f, f, f, vp]
+    lib.async_easgd_round.restype = i
+    lib.hogwild_easgd_round.argtypes = [vp, vp, vp, vp, i, sz, sz, f, f, f, vp]
+    lib.hogwild_easgd_round.restype = i
     ip = ctypes.POINTER(ctypes.c_int)
     lib.easgd_grad_workspace_bytes.argtypes = [ip, i, i, i]
     lib.easgd_grad_workspace_bytes.restype = sz
@@ -186,6 +190,31 @@ def sync_sgd_round(W, G, eta: float, V=None, delta: float = 0.0, N: Optional[int
     _check(_lib.sync_sgd_round(_dev("W", W, torch.float32, need),
                                None if V is None else _dev("V", V, torch.float32, need),
                                _dev("G", G, torch.float32, need), P, N, ld, eta, delta, _stream(stream)))
+
+
+def async_easgd_round(W, G, Wc, order: Sequence[int], eta: float, rho: float, V=None, delta: float = 0.0,
+                      N: Optional[int] = None, stream=None) -> None:
+    """The master serving one worker at a time in the sequence `order` (Algorithm 1 in rank order; Async EASGD /
+    Async MEASGD in arrival order), one launch for the whole schedule; V selects Eq. (5),(6)."""
+    P, ld, N = _replica_shape(W, N)
+    need = (P - 1) * ld + N
+    seq = (ctypes.c_int * len(order))(*[int(j) for j in order])
+    _check(_lib.async_easgd_round(_dev("W", W, torch.float32, need),
+                                  None if V is None else _dev("V", V, torch.float32, need),
+                                  _dev("G", G, torch.float32, need), _dev("Wc", Wc, torch.float32, N),
+                                  P, N, ld, seq, len(order), eta, rho, delta, _stream(stream)))
+
+
+def hogwild_easgd_round(W, G, Wc, eta: float, rho: float, V=None, delta: float = 0.0, N: Optional[int] = None,
+                        stream=None) -> None:
+    """Hogwild EASGD: all workers exchange with the center at once, lock-free (atomic adds into the center);
+    W and Wc are not reproducible from run to run."""
+    P, ld, N = _replica_shape(W, N)
+    need = (P - 1) * ld + N
+    _check(_lib.hogwild_easgd_round(_dev("W", W, torch.float32, need),
+                                    None if V is None else _dev("V", V, torch.float32, need),
+                                    _dev("G", G, torch.float32, need), _dev("Wc", Wc, torch.float32, N),
+                                    P, N, ld, eta, rho, delta, _stream(stream)))
 
 
 def _dims(dims: Sequence[int]):

@@ -1,4 +1,5 @@
-// Batched fp32 GEMM on the CDNA matrix cores (v_mfma_f32_32x32x2_f32) for the
+// Batched fp32 GEMM on the CDNA matrix cores (v_mfma_f32_32x32x2_f32, or
+// v_mfma_f32_16x16x4_f32 where a ragged batch would waste rows of a 32-row tile) for the
 // forward / backward passes of the per-worker dense models (Section 5.1 step (1),
 // Section 2.2).  One launch covers all P workers: every worker multiplies its
 // own operands, so the worker index is one more block coordinate.
@@ -14,7 +15,7 @@
 // more row of the same matrix product.
 //
 // Tiling: a block of WAVES_M x WAVES_N wavefronts owns a BM x BN tile of C; each
-// wavefront owns (BM/WAVES_M) x (BN/WAVES_N) of it as 32x32 MFMA accumulators.
+// wavefront owns (BM/WAVES_M) x (BN/WAVES_N) of it as 32x32 (MT = 32) or 16x16 (MT = 16) MFMA accumulators.
 // K is walked in slabs of BK with a prefetch distance of two slabs: global ->
 // registers (two stages) -> LDS (two buffers) -> MFMA operands.
 // LDS holds both operands k-major ([k][m] and [k][n], padded row pitch) so an
@@ -110,12 +111,13 @@ constexpr int gemm_lds_floats()
 
 // The work of block `bid` of one product.  `lds` is the calling kernel's buffer of at least
 // gemm_lds_floats<...>() floats, 16-byte aligned: kernels that carry two products lend the same buffer to both.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI, int MT = 32>
 __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid, float *__restrict__ lds)
 {
     constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int TM = WTM / MT, TN = WTN / MT;
+    static_assert(MT == 32 || MT == 16, "MFMA tile");
     // LDS row pitch: +4 keeps 128-bit row stores aligned for operands that arrive m/n-contiguous; operands that
     // arrive k-contiguous are scattered as scalars (lane -> k quad fastest), which is conflict-free when
     // 4*pitch = 32/(BK/4) mod 32, i.e. pitch = 1 mod 8 for BK = 32 and pitch = 2 mod 8 for BK = 16
@@ -125,7 +127,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     static_assert(BM % 8 == 0 && BN % 8 == 0, "tile shape");
     constexpr int CHUNKS_A = BM * BK / 4, CHUNKS_B = BN * BK / 4;
     constexpr int IT_A = (CHUNKS_A + NTHREADS - 1) / NTHREADS, IT_B = (CHUNKS_B + NTHREADS - 1) / NTHREADS;
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 4 == 0, "tile shape");
+    static_assert(WTM % MT == 0 && WTN % MT == 0 && BK % 4 == 0, "tile shape");
 
     float (*As)[BK * PITCH_A] = reinterpret_cast<float (*)[BK * PITCH_A]>(lds);
     float (*Bs)[BK * PITCH_B] = reinterpret_cast<float (*)[BK * PITCH_B]>(lds + 2 * BK * PITCH_A);
@@ -345,47 +347,60 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         }
     };
 
-    f32x16 acc[TM][TN];
+    constexpr int ACC_REGS = MT * MT / 64;
+    typedef float acc_t __attribute__((ext_vector_type(ACC_REGS)));
+    acc_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < ACC_REGS; ++r) acc[i][j][r] = 0.f;
 
-    // MFMA operand fetch: lane l supplies A[m = l%32][k = l/32] and B[k = l/32][n = l%32]
-    const int frag_k = lane >> 5, frag_x = lane & 31;
+    // MFMA operand fetch.  32x32x2: lane l supplies A[m = l%32][k = l/32] and B[k = l/32][n = l%32] of a k pair.
+    // 16x16x4: lane l supplies A[m = l%16] and B[n = l%16] at the k of its slot l/16.  Which k of the slab the
+    // four slots of one MFMA take is free as long as both operands agree; here MFMA j of a slab takes
+    // k = j, j + BK/4, j + BK/2, j + 3BK/4, with slots 0 and 1 (the lanes whose LDS reads are served together)
+    // BK/2 rows apart: for an operand that arrived k-contiguous (row pitch 1 mod 8 at BK = 32, 2 mod 8 at
+    // BK = 16) those two rows start 16 banks apart, so its reads do not collide.
+    constexpr int KSTEP = (MT == 32) ? 2 : 4;           // k consumed per MFMA
+    const int frag_k = (MT == 32) ? (lane >> 5) : (BK / 2) * ((lane >> 4) & 1) + (BK / 4) * (lane >> 5);
+    const int frag_x = lane & (MT - 1);
     // multiply the slab held in LDS buffer `buf`; k_left = number of valid k in it
     // `mid` runs after half of the full slab's MFMAs have been issued (used to move the next slab registers -> LDS
     // while the matrix pipeline is busy)
     auto multiply_slab = [&](int buf, int k_left, auto &&mid) {
         const float *as = &As[buf][frag_k * PITCH_A + wm0 + frag_x];
         const float *bs = &Bs[buf][frag_k * PITCH_B + wn0 + frag_x];
-        auto fetch = [&](int kk, float (&a)[TM], float (&b)[TN]) {
+        // step st: k pair 2*st of the slab (32x32x2), or rows st, st + BK/4, ... (16x16x4)
+        auto fetch = [&](int st, float (&a)[TM], float (&b)[TN]) {
+            const int kk = (MT == 32) ? 2 * st : st;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = as[kk * PITCH_A + i * 32];
+            for (int i = 0; i < TM; ++i) a[i] = as[kk * PITCH_A + i * MT];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = bs[kk * PITCH_B + j * 32];
+            for (int j = 0; j < TN; ++j) b[j] = bs[kk * PITCH_B + j * MT];
         };
         auto multiply = [&](const float (&a)[TM], const float (&b)[TN]) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (MT == 32) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                    else acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                }
         };
+        constexpr int STEPS = BK / KSTEP;
         if (k_left >= BK) {
-            // operands are fetched from LDS DIST k pairs ahead of the MFMAs that use them, so the LDS
-            // latency hides behind the matrix pipeline (one pair ahead = 4 MFMAs when a wave owns 2x2
-            // tiles; two pairs ahead when it owns a single tile)
+            // operands are fetched from LDS DIST steps ahead of the MFMAs that use them, so the LDS
+            // latency hides behind the matrix pipeline (one step ahead = 4 MFMAs when a wave owns 2x2
+            // tiles; two steps ahead when it owns a single tile)
             constexpr int DIST = (TM * TN == 1) ? 2 : 1;
-            constexpr int STEPS = BK / 2;
             float a[DIST + 1][TM], b[DIST + 1][TN];
 #pragma unroll
-            for (int d = 0; d < DIST; ++d) fetch(2 * d, a[d], b[d]);
+            for (int d = 0; d < DIST; ++d) fetch(d, a[d], b[d]);
 #pragma unroll
             for (int st = 0; st < STEPS; ++st) {
-                if (st + DIST < STEPS) fetch(2 * (st + DIST), a[(st + DIST) % (DIST + 1)], b[(st + DIST) % (DIST + 1)]);
+                if (st + DIST < STEPS) fetch(st + DIST, a[(st + DIST) % (DIST + 1)], b[(st + DIST) % (DIST + 1)]);
                 __builtin_amdgcn_sched_barrier(0);      // keep the LDS reads ahead of the MFMAs below
                 multiply(a[st % (DIST + 1)], b[st % (DIST + 1)]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -395,10 +410,12 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                 }
             }
         } else {
-            // short slab: stop at the last k pair that holds data (the rest of the slab is zero)
-            for (int kk = 0; kk < k_left; kk += 2) {
+            // short slab: stop at the last step that holds data (the rest of the slab is zero); with 16x16x4
+            // step st holds k = st and three rows further down, so the steps below k_left are the ones to take
+            const int n_steps = (MT == 32) ? (k_left + 1) / 2 : min(k_left, STEPS);
+            for (int st = 0; st < n_steps; ++st) {
                 float a[TM], b[TN];
-                fetch(kk, a, b);
+                fetch(st, a, b);
                 multiply(a, b);
             }
             mid();
@@ -520,8 +537,44 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     unsigned short *__restrict__ Vr16 = MOM16 ? p.Vt16 + (size_t)w * p.c_ws : nullptr;
     const float *__restrict__ Cc = ELASTIC ? p.center : nullptr;
     const int wave_m = __builtin_amdgcn_readfirstlane(m0 + wm0), wave_n = __builtin_amdgcn_readfirstlane(n0 + wn0);
-    const unsigned lane_c = (unsigned)(4 * frag_k) * (unsigned)p.ldc + (unsigned)frag_x;
-    const unsigned lane_mask = (unsigned)(4 * frag_k) * (unsigned)p.ldmask + (unsigned)frag_x;
+    const int frag_r = 4 * (lane / MT);     // first row of the lane's accumulator registers inside an MFMA tile
+    const unsigned lane_c = (unsigned)frag_r * (unsigned)p.ldc + (unsigned)frag_x;
+    const unsigned lane_mask = (unsigned)frag_r * (unsigned)p.ldmask + (unsigned)frag_x;
+    if constexpr (MT == 16) {
+        // 16x16 accumulators: register r of lane l is C[4*(l/16) + r][l%16] of its tile.  The block tile is as
+        // tall as the ragged batch rounded up to 16 rows, so the last rows of tiles are the common case here, not
+        // an edge: a row of tiles that lies inside C (block-uniform test) stores without bounds checks, the one
+        // that straddles the last row of C checks rows only.
+        static_assert(!ELASTIC && !OUT16, "the 16x16 tiles serve the forward and input-gradient products");
+        const bool cols_inside = (n0 + BN <= p.N);                                    // uniform
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mt = wave_m + i * 16;                                           // uniform
+            if (mt >= p.M) break;
+            const bool inside = cols_inside && mt + 16 <= p.M;
+            float gate[TN][4];
+            if (EPI == EPI_MASK) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const bool ok = inside || (mt + frag_r + r < p.M && wave_n + j * 16 + frag_x < p.N);
+                        gate[j][r] = ok ? (mask + (size_t)(mt + r) * p.ldmask + wave_n + j * 16)[lane_mask] : 0.f;
+                    }
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = acc[i][j][r];
+                    if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
+                    if (EPI == EPI_MASK) v = (gate[j][r] > 0.f) ? v : 0.f;
+                    if (inside || (mt + frag_r + r < p.M && wave_n + j * 16 + frag_x < p.N))
+                        (C + (size_t)(mt + r) * p.ldc + wave_n + j * 16)[lane_c] = v;
+                }
+        }
+        return;
+    }
     if (m0 + BM <= p.M && n0 + BN <= p.N) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -578,7 +631,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                 const int n = n0 + wn0 + j * 32 + frag_x;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * frag_k + (r % 4);
+                    const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
                     if (m < p.M && n < p.N) {
                         float v = acc[i][j][r];
                         const size_t at = (size_t)m * p.ldc + n;
@@ -607,7 +660,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
 }
 
 // One product per launch; the grid may be extended by blocks that run the center rule (p.ctr).
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI, int MT = 32>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(GemmArgs p)
 {
     __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<BM, BN, BK, A_LAYOUT, B_LAYOUT>()];
@@ -617,7 +670,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
         else center_rule_block<float>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
         return;
     }
-    gemm_block<BM, BN, BK, WAVES_M, WAVES_N, A_LAYOUT, B_LAYOUT, VEC, EPI>(p, blockIdx.x, lds);
+    gemm_block<BM, BN, BK, WAVES_M, WAVES_N, A_LAYOUT, B_LAYOUT, VEC, EPI, MT>(p, blockIdx.x, lds);
 }
 
 // Two independent products in one launch: blocks [0, n0) work on p0 with the first configuration, the rest on

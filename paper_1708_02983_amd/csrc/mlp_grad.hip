@@ -259,7 +259,7 @@ static void launch_pair_dw_dw(GemmArgs d0, GemmArgs d1, hipStream_t s)
                        dim3(n0 + n1), dim3(256), 0, s, d0, d1, n0);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int AL, int BL, int EPI>
+template <int BM, int BN, int BK, int WM, int WN, int AL, int BL, int EPI, int MT = 32>
 static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
 {
     GemmArgs a = a_in;
@@ -270,8 +270,20 @@ static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
         total += a.ctr.blocks;
     }
     const dim3 grid((unsigned)total), block(WM * WN * 64);
-    if (vec) EASGD_LAUNCH((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, true, EPI>), grid, block, 0, s, a);
-    else EASGD_LAUNCH((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI>), grid, block, 0, s, a);
+    if (vec) EASGD_LAUNCH((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, true, EPI, MT>), grid, block, 0, s, a);
+    else EASGD_LAUNCH((gemm_mfma_kernel<BM, BN, BK, WM, WN, AL, BL, false, EPI, MT>), grid, block, 0, s, a);
+}
+
+// A batch that is not a multiple of 32 rows wastes matrix-core time in 32-row MFMA tiles (b = 100: 128 rows are
+// multiplied, 28 % more than stored).  The 16x16x4 instruction has the same rate, so a block tile of 7 x 16 = 112 rows
+// by 128 columns (four wavefronts side by side, 7 x 2 accumulators each) multiplies 112.  It is chosen for the
+// products whose M is the batch (forward, input gradient) when it covers M with fewer rows than 32-row tiles do
+// and still gives every compute unit about two blocks.
+static bool tile16_pays(int M, int N, int P, int splits)
+{
+    const long rows16 = (long)((M + 111) / 112) * 112, rows32 = (long)((M + 31) / 32) * 32;
+    if (N <= 32 || rows16 >= rows32) return false;
+    return (size_t)((M + 111) / 112) * ((N + 127) / 128) * splits * P >= (size_t)(2 * num_cus());
 }
 
 // Picks the tile shape.  Outputs at most 32 wide use a 128x32 tile.  Otherwise 64x64 blocks (four per
@@ -287,6 +299,13 @@ static void launch_gemm(const GemmArgs &a, bool vec, bool large_ok, hipStream_t 
     }
     const size_t big = (size_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.splits * a.P;
     long tile = options().gemm_tile;
+    if constexpr (AL == K_CONTIG && (EPI == EPI_NONE || EPI == EPI_RELU || EPI == EPI_MASK)) {
+        if (tile == 4 || (tile == 0 && tile16_pays(a.M, a.N, a.P, a.splits))) {
+            launch_tile<112, 128, 32, 1, 4, AL, BL, EPI, 16>(a, vec, s);
+            return;
+        }
+    }
+    if (tile == 4) tile = 0;            // the weight-gradient products have no 16-row form
     if (tile == 0) tile = (large_ok && big >= (size_t)(2 * num_cus())) ? 1 : 2;
     if (tile == 1) launch_tile<128, 128, 16, 2, 2, AL, BL, EPI>(a, vec, s);
     else if (tile == 2) launch_tile<64, 64, 32, 2, 2, AL, BL, EPI>(a, vec, s);
@@ -304,6 +323,7 @@ static bool forward_launch_has_room(int M, int N, int P, int splits)
     const size_t cus = (size_t)num_cus();
     if (N <= 32) return (size_t)((M + 127) / 128) * splits * P <= 3 * cus;
     long tile = options().gemm_tile;
+    if (tile == 4 || (tile == 0 && tile16_pays(M, N, P, splits))) return false;
     const size_t big = (size_t)((M + 127) / 128) * ((N + 127) / 128) * splits * P;
     if (tile == 0) tile = (big >= 2 * cus) ? 1 : 2;
     if (tile != 2) return false;

@@ -96,7 +96,7 @@ int easgd_set_option(int option, long value)
         o.update_groups = value;
         return EASGD_OK;
     case EASGD_OPT_GEMM_TILE:
-        if (value < 0 || value > 3) return easgd::fail(EASGD_EINVAL, "gemm tile must be in [0,3], got %ld", value);
+        if (value < 0 || value > 4) return easgd::fail(EASGD_EINVAL, "gemm tile must be in [0,4], got %ld", value);
         o.gemm_tile = value;
         return EASGD_OK;
     case EASGD_OPT_ROUND_OVERLAP:

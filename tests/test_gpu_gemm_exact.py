@@ -88,7 +88,7 @@ def test_reference_is_the_triple_loop():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("d_in,d_out,P,b", SHAPES, ids=lambda v: str(v))
 def test_each_product_is_exact_on_integers(d_in, d_out, P, b, tile):
     import paper_1708_02983_amd as hip

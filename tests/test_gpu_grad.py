@@ -110,7 +110,7 @@ def test_full_shape_one_round(hip, name):
     assert np.isfinite(G[:, :N]).all()
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 def test_every_tile_shape_gives_the_same_gradient(hip, tile):
     """The block-tile option only changes the launch shape: each forced shape must match the oracle."""
     dims, P, b = (200, 264, 136, 10), 3, 100

@@ -99,7 +99,7 @@ def test_fused_round_equals_gradient_then_update(hip, dims, P, b, momentum):
         hip.set_option(hip.OPT_ROUND_OVERLAP, old)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 def test_every_tile_shape_gives_the_same_round(hip, tile):
     dims, P, b = (300, 260, 200, 10), 6, 70
     N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=32)

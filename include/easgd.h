@@ -364,7 +364,9 @@ typedef enum {
     EASGD_OPT_UPDATE_GROUPS        = 3,  /* 128-bit groups per thread and worker: 1, 2, 4 or 8; 0 = chosen per call (default): 4, fewer
                                             when N is small */
     EASGD_OPT_GEMM_TILE            = 4,  /* block tile of the wide matrix products of easgd_grad: 0 = chosen per product (default),
-                                            1 = 128x128, 2 = 64x64, 3 = 128x64 */
+                                            1 = 128x128, 2 = 64x64, 3 = 128x64, 4 = 48, 80 or 112 rows by 128 columns in 16x16x4 matrix
+                                            instructions for the products whose rows are the minibatch (chosen by default when
+                                            one of these heights covers b with fewer rows than b rounded up to 32, e.g. b = 100) */
     EASGD_OPT_ROUND_OVERLAP        = 5,  /* easgd_mlp_round, where the center rule runs: 0 = a kernel of its own on the caller's
                                             stream; 2 = the same on a second stream of the library, beside forward propagation;
                                             3 = on extra blocks of the first forward product's launch; 1 = chosen per call

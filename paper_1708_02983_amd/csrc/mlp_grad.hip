@@ -275,15 +275,25 @@ static void launch_tile(const GemmArgs &a_in, bool vec, hipStream_t s)
 }
 
 // A batch that is not a multiple of 32 rows wastes matrix-core time in 32-row MFMA tiles (b = 100: 128 rows are
-// multiplied, 28 % more than stored).  The 16x16x4 instruction has the same rate, so a block tile of 7 x 16 = 112 rows
-// by 128 columns (four wavefronts side by side, 7 x 2 accumulators each) multiplies 112.  It is chosen for the
-// products whose M is the batch (forward, input gradient) when it covers M with fewer rows than 32-row tiles do
-// and still gives every compute unit about two blocks.
-static bool tile16_pays(int M, int N, int P, int splits)
+// multiplied, 28 % more than stored).  The 16x16x4 instruction has the same rate, so a block tile of 3, 5 or 7 x 16
+// rows by 128 columns (four wavefronts side by side, 3, 5 or 7 x 2 accumulators each) multiplies 48, 80 or 112
+// rows per tile.  It is chosen for the products whose M is the batch (forward, input gradient) when one of the
+// three heights covers M with fewer rows than 32-row tiles do and still gives every compute unit about two
+// blocks.  Returns that height, or 0.
+static int tile16_rows(int M, int N, int P, int splits)
 {
-    const long rows16 = (long)((M + 111) / 112) * 112, rows32 = (long)((M + 31) / 32) * 32;
-    if (N <= 32 || rows16 >= rows32) return false;
-    return (size_t)((M + 111) / 112) * ((N + 127) / 128) * splits * P >= (size_t)(2 * num_cus());
+    if (N <= 32) return 0;
+    long best_rows = (long)((M + 31) / 32) * 32;
+    int best = 0;
+    for (int bm : {112, 80, 48}) {
+        const long rows = (long)((M + bm - 1) / bm) * bm;
+        if (rows < best_rows) {
+            best_rows = rows;
+            best = bm;
+        }
+    }
+    if (best == 0) return 0;
+    return (size_t)((M + best - 1) / best) * ((N + 127) / 128) * splits * P >= (size_t)(2 * num_cus()) ? best : 0;
 }
 
 // Picks the tile shape.  Outputs at most 32 wide use a 128x32 tile.  Otherwise 64x64 blocks (four per
@@ -300,10 +310,12 @@ static void launch_gemm(const GemmArgs &a, bool vec, bool large_ok, hipStream_t 
     const size_t big = (size_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.splits * a.P;
     long tile = options().gemm_tile;
     if constexpr (AL == K_CONTIG && (EPI == EPI_NONE || EPI == EPI_RELU || EPI == EPI_MASK)) {
-        if (tile == 4 || (tile == 0 && tile16_pays(a.M, a.N, a.P, a.splits))) {
-            launch_tile<112, 128, 32, 1, 4, AL, BL, EPI, 16>(a, vec, s);
-            return;
-        }
+        int bm16 = (tile == 0) ? tile16_rows(a.M, a.N, a.P, a.splits) : 0;
+        if (tile == 4) bm16 = a.M <= 48 ? 48 : a.M <= 80 ? 80 : 112;    // forced: the smallest height that covers M, else 112
+        if (bm16 == 112) launch_tile<112, 128, 32, 1, 4, AL, BL, EPI, 16>(a, vec, s);
+        else if (bm16 == 80) launch_tile<80, 128, 32, 1, 4, AL, BL, EPI, 16>(a, vec, s);
+        else if (bm16 == 48) launch_tile<48, 128, 32, 1, 4, AL, BL, EPI, 16>(a, vec, s);
+        if (bm16) return;
     }
     if (tile == 4) tile = 0;            // the weight-gradient products have no 16-row form
     if (tile == 0) tile = (large_ok && big >= (size_t)(2 * num_cus())) ? 1 : 2;
@@ -323,7 +335,7 @@ static bool forward_launch_has_room(int M, int N, int P, int splits)
     const size_t cus = (size_t)num_cus();
     if (N <= 32) return (size_t)((M + 127) / 128) * splits * P <= 3 * cus;
     long tile = options().gemm_tile;
-    if (tile == 4 || (tile == 0 && tile16_pays(M, N, P, splits))) return false;
+    if (tile == 4 || (tile == 0 && tile16_rows(M, N, P, splits) != 0)) return false;
     const size_t big = (size_t)((M + 127) / 128) * ((N + 127) / 128) * splits * P;
     if (tile == 0) tile = (big >= 2 * cus) ? 1 : 2;
     if (tile != 2) return false;

@@ -4,7 +4,7 @@ the k sum, so the MFMA kernels must reproduce a plain triple loop BIT FOR BIT.  
 twice or read past its end, a wrong ones row (bias), a transposed operand or a tile written to the wrong place
 cannot hide under a rounding tolerance here.  Every operand-layout combination (forward: k-contiguous x
 n-contiguous; weight gradient: m-contiguous x n-contiguous; input gradient: k-contiguous x k-contiguous), every
-tile shape, K not a multiple of the slab depth, ragged M and N, the tile that holds the ones row, operands that
+tile shape (the 16x16x4 tiles in all three heights, forced and chosen by default), K not a multiple of the slab depth, ragged M and N, the tile that holds the ones row, operands that
 rule out 128-bit loads, and enough workers for the die-aware block order."""
 import numpy as np
 import pytest
@@ -24,6 +24,9 @@ SHAPES = [
     (36, 32, 4, 44),        # N = 32 exactly
     (512, 256, 8, 128),     # >= 64 tiles: die-aware renumbering; several k slabs per block
     (300, 260, 16, 70),     # many workers, ragged everything, multiples of 4
+    (64, 2048, 32, 40),     # enough blocks for the 16-row MFMA tiles to be chosen by default: 48 rows for b = 40,
+    (60, 2048, 32, 72),     # 80 rows for b = 72,
+    (64, 2048, 32, 100),    # 112 rows for b = 100
 ]
 
 

@@ -150,7 +150,8 @@ def test_options_roundtrip(lib):
     assert lib.easgd_set_option(5, 2) == 0 and lib.easgd_get_option(5) == 2 and lib.easgd_set_option(5, 1) == 0
     assert lib.easgd_get_option(6) == 1 and lib.easgd_set_option(6, 4) == -1 and lib.easgd_set_option(6, 3) == 0 and lib.easgd_set_option(6, 1) == 0
     assert lib.easgd_set_option(6, 0) == 0 and lib.easgd_get_option(6) == 0 and lib.easgd_set_option(6, 1) == 0
-    assert lib.easgd_get_option(4) == 0 and lib.easgd_set_option(4, 4) == -1
+    assert lib.easgd_get_option(4) == 0 and lib.easgd_set_option(4, 5) == -1
+    assert lib.easgd_set_option(4, 4) == 0 and lib.easgd_get_option(4) == 4 and lib.easgd_set_option(4, 0) == 0
     assert lib.easgd_get_option(7) == 1 and lib.easgd_set_option(7, 2) == -1 and lib.easgd_set_option(7, 1) == 0
     assert lib.easgd_get_option(8) == 1 and lib.easgd_set_option(8, 2) == -1
     assert lib.easgd_set_option(8, 0) == 0 and lib.easgd_get_option(8) == 0 and lib.easgd_set_option(8, 1) == 0

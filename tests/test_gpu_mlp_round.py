@@ -119,6 +119,29 @@ def test_every_tile_shape_gives_the_same_round(hip, tile):
         assert normwise(a[..., :N], c[..., :N]) <= 1e-6
 
 
+@pytest.mark.parametrize("tile", [1, 3, 4])
+def test_center_rule_rides_on_every_forward_tile(hip, tile):
+    """The center rule on extra blocks of the first forward launch, whatever tile shape that launch uses (by default the
+    extra blocks are only attached to 64x64 launches): same bits as the rule run as a kernel of its own."""
+    dims, P, b = (300, 260, 200, 10), 6, 100
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=33)
+    dX, dy = to_dev(X), to_dev(y)
+    old = hip.get_option(hip.OPT_GEMM_TILE), hip.get_option(hip.OPT_ROUND_OVERLAP)
+    out = []
+    try:
+        hip.set_option(hip.OPT_GEMM_TILE, tile)
+        for overlap in (0, 3):
+            hip.set_option(hip.OPT_ROUND_OVERLAP, overlap)
+            fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
+            hip.easgd_mlp_round(dims, fW, fWc, dX, dy, ETA, RHO, V=fV, delta=DELTA)
+            out.append((to_host(fW), to_host(fV), to_host(fWc)))
+    finally:
+        hip.set_option(hip.OPT_GEMM_TILE, old[0])
+        hip.set_option(hip.OPT_ROUND_OVERLAP, old[1])
+    for a, c in zip(out[0], out[1]):
+        np.testing.assert_array_equal(a, c)
+
+
 def test_consecutive_rounds_on_one_stream_and_reproducibility(hip):
     """Several fused rounds back to back, overlapped and not: the rounds are ordered correctly on the
     caller's stream (each starts from the previous one's results) and runs are bitwise reproducible."""

@@ -111,7 +111,7 @@ constexpr int gemm_lds_floats()
 
 // The work of block `bid` of one product.  `lds` is the calling kernel's buffer of at least
 // gemm_lds_floats<...>() floats, 16-byte aligned: kernels that carry two products lend the same buffer to both.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI, int MT = 32>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int A_LAYOUT, int B_LAYOUT, bool VEC, int EPI, int MT = 32, bool ALONE = false>
 __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid, float *__restrict__ lds)
 {
     constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
@@ -465,6 +465,30 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     // one barrier per slab.
     f32x4 ra0[IT_A], rb0[IT_B], ra1[IT_A], rb1[IT_B];
     int s_done = 0;
+    // The narrow tile with the worker rule in its epilogue (the weight gradient of a last layer of a few classes; a
+    // softmax regression has nothing else) is a chain of round trips to memory on a chip that is otherwise idle:
+    // operands, then the replica, center and momentum tiles.  Its epilogue's tiles are requested here, before the
+    // operands, so that the two trips become one.  (The wide tiles do not do this: their launches fill the chip, and
+    // requests made this early only queue ahead of the operand loads of the blocks that share the compute unit; nor
+    // does a narrow product that shares its launch with a wide one, ALONE = false: the registers would cost the wide
+    // product a block per compute unit.)
+    constexpr bool ELASTIC_EPI = (EPI == EPI_ELASTIC || EPI == EPI_ELASTIC_MOM || EPI == EPI_ELASTIC_MOM_BF16);
+    constexpr bool EARLY_TILES = ALONE && ELASTIC_EPI && BN == 32 && TM == 1 && TN == 1 && MT == 32;
+    float pre_w[EARLY_TILES ? 16 : 1], pre_c[EARLY_TILES ? 16 : 1], pre_v[EARLY_TILES ? 16 : 1];
+    unsigned short pre_v16[EARLY_TILES ? 16 : 1];
+    if constexpr (EARLY_TILES) {
+        const int n = n0 + wn0 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm0 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+            const size_t at = (size_t)m * p.ldc + n;
+            const bool ok = m < p.M && n < p.N;
+            pre_w[r] = ok ? (p.Wt + (size_t)w * p.c_ws)[at] : 0.f;
+            pre_c[r] = ok ? p.center[at] : 0.f;
+            pre_v[r] = (EPI == EPI_ELASTIC_MOM && ok) ? (p.Vt + (size_t)w * p.c_ws)[at] : 0.f;
+            pre_v16[r] = (EPI == EPI_ELASTIC_MOM_BF16 && ok) ? (p.Vt16 + (size_t)w * p.c_ws)[at] : (unsigned short)0;
+        }
+    }
     if (n_pipe >= 2) {
         load_slab(0, ra0, rb0);
         load_slab(1, ra1, rb1);
@@ -511,20 +535,44 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
         __syncthreads();
         s_done = n_pipe;
     }
-    // Otherwise (operands that do not allow 128-bit loads, or a single slab): load, store, multiply, one at a time.
-    for (int s = s_done; s < n_slabs; ++s) {
-        const int k0 = k_begin + s * BK;
-        load_guarded(k0, ra0, rb0);
-        store_lds(0, ra0, rb0, false);
-        __syncthreads();
-        multiply_slab(0, k_end - k0, nothing);
-        __syncthreads();
+    // Otherwise (operands that do not allow 128-bit loads, or a single slab).  Kernels built for such operands take
+    // two slabs per trip, both requested before the first is waited for, so that a short product (K = the minibatch:
+    // two to four slabs) pays one round trip to memory per pair of slabs instead of one per slab.  The kernels of the
+    // 128-bit path only come here with a single slab, and keep the plain loop: the second register stage in this
+    // path costs them registers that the center rule's wavefronts need to run beside them (cfg3's forward launch:
+    // 228 -> 246 registers, the round 2.37 -> 2.51 ms).
+    if constexpr (!VEC) {
+        for (int s = s_done; s < n_slabs; s += 2) {
+            const int k0 = k_begin + s * BK;
+            const bool two = s + 1 < n_slabs;                 // uniform; slab s is then a full one
+            load_guarded(k0, ra0, rb0);
+            if (two) load_guarded(k0 + BK, ra1, rb1);
+            store_lds(0, ra0, rb0, false);
+            __syncthreads();
+            if (two) {
+                multiply_slab(0, BK, [&] { store_lds(1, ra1, rb1, false); });
+                __syncthreads();
+                multiply_slab(1, k_end - (k0 + BK), nothing);
+            } else {
+                multiply_slab(0, k_end - k0, nothing);
+            }
+            __syncthreads();
+        }
+    } else {
+        for (int s = s_done; s < n_slabs; ++s) {
+            const int k0 = k_begin + s * BK;
+            load_guarded(k0, ra0, rb0);
+            store_lds(0, ra0, rb0, false);
+            __syncthreads();
+            multiply_slab(0, k_end - k0, nothing);
+            __syncthreads();
+        }
     }
 
     // epilogue: accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
     // Addresses are split into a block-uniform row pointer (scalar arithmetic) and one 32-bit lane offset
     // that is computed once; tiles that lie fully inside C skip the per-element bounds checks.
-    constexpr bool ELASTIC = (EPI == EPI_ELASTIC || EPI == EPI_ELASTIC_MOM || EPI == EPI_ELASTIC_MOM_BF16);
+    constexpr bool ELASTIC = ELASTIC_EPI;
     constexpr bool MOM = (EPI == EPI_ELASTIC_MOM);
     constexpr bool MOM16 = (EPI == EPI_ELASTIC_MOM_BF16);
     constexpr bool OUT16 = (EPI == EPI_STORE_BF16);
@@ -586,6 +634,10 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                     unsigned short v16[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {  // all loads of the tile first, so that they overlap
+                        if constexpr (EARLY_TILES) {        // requested before the K loop
+                            wv[r] = pre_w[r]; cv[r] = pre_c[r]; vv[r] = pre_v[r]; v16[r] = pre_v16[r];
+                            continue;
+                        }
                         const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
                         wv[r] = (Wr + row)[lane_c];
                         cv[r] = (Cc + row)[lane_c];
@@ -629,30 +681,55 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn0 + j * 32 + frag_x;
+                if constexpr (ELASTIC) {
+                    // Three passes over the tile, as in the full-tile path: every load, then the rule, then every
+                    // store.  Written element by element (load, rule, store, next element) the stores to the replica
+                    // keep the next element's loads from the same array behind them, and a narrow layer, all of whose
+                    // tiles are edge tiles, pays sixteen round trips to memory in a row.
+                    float wv[16], cv[16], vv[16];
+                    unsigned short v16[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
+                        const size_t at = (size_t)m * p.ldc + n;
+                        const bool ok = m < p.M && n < p.N;
+                        if constexpr (EARLY_TILES) {        // requested before the K loop
+                            wv[r] = pre_w[r]; cv[r] = pre_c[r]; vv[r] = pre_v[r]; v16[r] = pre_v16[r];
+                            continue;
+                        }
+                        wv[r] = ok ? Wr[at] : 0.f;
+                        cv[r] = ok ? Cc[at] : 0.f;
+                        vv[r] = (MOM && ok) ? Vr[at] : 0.f;
+                        v16[r] = (MOM16 && ok) ? Vr16[at] : (unsigned short)0;
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if constexpr (MOM16) worker_rule_bf16<true>(wv[r], v16[r], acc[i][j][r], cv[r], p.eta, p.rho, p.alpha, p.delta);
+                        else worker_rule<MOM>(wv[r], vv[r], acc[i][j][r], cv[r], p.eta, p.rho, p.alpha, p.delta);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
+                        const size_t at = (size_t)m * p.ldc + n;
+                        if (m < p.M && n < p.N) {
+                            Wr[at] = wv[r];
+                            if (MOM) Vr[at] = vv[r];
+                            if (MOM16) Vr16[at] = v16[r];
+                            if (keep) C[at] = acc[i][j][r];
+                        }
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
                     if (m < p.M && n < p.N) {
                         float v = acc[i][j][r];
                         const size_t at = (size_t)m * p.ldc + n;
-                        if constexpr (ELASTIC) {
-                            float wv = Wr[at], vv = MOM ? Vr[at] : 0.f;
-                            if constexpr (MOM16) {
-                                unsigned short v16 = Vr16[at];
-                                worker_rule_bf16<true>(wv, v16, v, Cc[at], p.eta, p.rho, p.alpha, p.delta);
-                                Vr16[at] = v16;
-                            } else {
-                                worker_rule<MOM>(wv, vv, v, Cc[at], p.eta, p.rho, p.alpha, p.delta);
-                            }
-                            Wr[at] = wv;
-                            if (MOM) Vr[at] = vv;
-                            if (keep) C[at] = v;
-                        } else {
-                            if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
-                            if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
-                            if constexpr (OUT16) C16[at] = bf16_narrow(v);
-                            else C[at] = v;
-                        }
+                        if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
+                        if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
+                        if constexpr (OUT16) C16[at] = bf16_narrow(v);
+                        else C[at] = v;
                     }
                 }
             }
@@ -670,7 +747,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, 2) void gemm_mfma_kernel(Gem
         else center_rule_block<float>(p.ctr.W, p.ctr.Wc, p.ctr.old, p.ctr.P, p.ctr.N, p.ctr.ld, p.ctr.alpha, b, p.ctr.blocks, threadIdx.x);
         return;
     }
-    gemm_block<BM, BN, BK, WAVES_M, WAVES_N, A_LAYOUT, B_LAYOUT, VEC, EPI, MT>(p, blockIdx.x, lds);
+    gemm_block<BM, BN, BK, WAVES_M, WAVES_N, A_LAYOUT, B_LAYOUT, VEC, EPI, MT, true>(p, blockIdx.x, lds);
 }
 
 // Two independent products in one launch: blocks [0, n0) work on p0 with the first configuration, the rest on

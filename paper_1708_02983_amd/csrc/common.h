@@ -50,8 +50,9 @@ int elastic_range(float *W, float *V, const float *G, float *Wc, int P, size_t N
                   float eta, float rho, float delta, void *stream);
 
 // Eq. (2) alone, ahead of the worker rules: Wc[j] <- Wc[j] + alpha * sum_i (W_i[j] - Wc[j]), ascending i;
-// the time-t center is saved to old[0..N).
-int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t ld, float alpha, void *stream);
+// the time-t center is saved to old[0..N).  beside: the launch runs on a stream of its own beside matrix products
+// (then it takes one block per compute unit, see the definition).
+int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t ld, float alpha, void *stream, bool beside = false);
 
 // Where the streaming update kernels find their parameters.  A block of 256 threads handles GROUPS groups of four
 // consecutive parameters per thread: thread `tid` of block `t` owns groups first(t, tid) + q * STRIDE, q < GROUPS.

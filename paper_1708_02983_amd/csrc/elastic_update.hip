@@ -301,13 +301,35 @@ __global__ __launch_bounds__(256) void center_rule_kernel(const float *__restric
     center_rule_block<T>(Wp, Wcp, oldp, P, N, ld, alpha, blockIdx.x, gridDim.x, threadIdx.x);
 }
 
-int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t ld, float alpha, void *stream)
+// The same with a grid of any size: block x does the work of blocks x, x + gridDim.x, ... of the kernel above.
+template <typename T>
+__global__ __launch_bounds__(256) void center_rule_walk_kernel(const float *__restrict__ Wp, float *__restrict__ Wcp,
+                                                               float *__restrict__ oldp, int P, size_t N, size_t ld,
+                                                               float alpha, unsigned n_blocks)
+{
+    for (unsigned b = blockIdx.x; b < n_blocks; b += gridDim.x)
+        center_rule_block<T>(Wp, Wcp, oldp, P, N, ld, alpha, b, n_blocks, threadIdx.x);
+}
+
+int center_range(const float *W, float *Wc, float *old, int P, size_t N, size_t ld, float alpha, void *stream, bool beside)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = aligned16(W) && aligned16(Wc) && aligned16(old) && (ld % 4 == 0);
     const size_t units = vec ? N / 4 : N;
     const size_t blocks = units / 256 + 1;    // the last block also owns the scalar tail
     if (blocks > 0x7fffffffu) return fail(EASGD_ERANGE, "center rule: N too large");
+    // Beside the matrix products of forward propagation (on the library's second stream): one block per compute
+    // unit that walks the parameter range.  A forward launch leaves each SIMD the registers of about one more
+    // small wavefront; thousands of short blocks keep competing for that slot with each other and with the
+    // products' own block turnover, one resident block per compute unit just streams.  Measured at P = 32,
+    // N = 10.5 M: the two forward launches 2 x 381 -> 2 x 340 us (308 us alone), the round 2.37 -> 2.27 ms;
+    // 192 to 256 blocks are equal, 288 and more or 128 and fewer are slower than the short blocks.
+    const size_t cus = (size_t)num_cus();
+    if (beside && blocks > 4 * cus) {
+        if (vec) EASGD_LAUNCH((center_rule_walk_kernel<f32x4>), dim3((unsigned)cus), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha, (unsigned)blocks);
+        else EASGD_LAUNCH((center_rule_walk_kernel<float>), dim3((unsigned)cus), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha, (unsigned)blocks);
+        return check_launch("center rule");
+    }
     if (vec) EASGD_LAUNCH((center_rule_kernel<f32x4>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
     else EASGD_LAUNCH((center_rule_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, W, Wc, old, P, N, ld, alpha);
     return check_launch("center rule");

@@ -573,7 +573,7 @@ static int grad_impl(const char *name, const int *dims, int n_layers, const floa
         if (lane) {
             if (hipEventRecord(lane->fork, s) != hipSuccess || hipStreamWaitEvent(lane->stream, lane->fork, 0) != hipSuccess)
                 return check_launch(name) != EASGD_OK ? EASGD_ELAUNCH : fail(EASGD_ELAUNCH, "%s: stream fork failed", name);
-            rc = center_range(step->W, step->Wc, old_center, P, pl.N, ld, alpha, lane->stream);
+            rc = center_range(step->W, step->Wc, old_center, P, pl.N, ld, alpha, lane->stream, true);
             if (rc == EASGD_OK && hipEventRecord(lane->join, lane->stream) != hipSuccess)
                 rc = fail(EASGD_ELAUNCH, "%s: stream join failed", name);
         } else if (!attach_center) {

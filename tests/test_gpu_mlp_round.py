@@ -142,6 +142,30 @@ def test_center_rule_rides_on_every_forward_tile(hip, tile):
         np.testing.assert_array_equal(a, c)
 
 
+@pytest.mark.parametrize("dims,P,b,ld_pad", [((1024, 1100, 10), 2, 8, 0), ((512, 600, 10), 3, 16, 1)],
+                         ids=["vector", "scalar"])
+def test_center_rule_beside_forward_walks_the_range(hip, dims, P, b, ld_pad):
+    """On the second stream the center rule of a long parameter vector takes one block per compute unit that walks
+    the range (128-bit form, and the scalar form for a row stride that is no multiple of 4): same bits as the rule
+    as a kernel of its own, padding untouched."""
+    N, ld, W, V, Wc, X, y = _state(dims, P, b, seed=34, ld_pad=ld_pad)
+    dX, dy = to_dev(X), to_dev(y)
+    old = hip.get_option(hip.OPT_ROUND_OVERLAP)
+    out = []
+    try:
+        for overlap in (0, 2):
+            hip.set_option(hip.OPT_ROUND_OVERLAP, overlap)
+            fW, fV, fWc = to_dev(W), to_dev(V), to_dev(Wc)
+            hip.easgd_mlp_round(dims, fW, fWc, dX, dy, ETA, RHO, V=fV, delta=DELTA)
+            out.append((to_host(fW), to_host(fV), to_host(fWc)))
+    finally:
+        hip.set_option(hip.OPT_ROUND_OVERLAP, old)
+    for a, c in zip(out[0], out[1]):
+        np.testing.assert_array_equal(a, c)
+    assert not np.array_equal(out[1][2], Wc)                    # the center did move
+    assert np.isnan(out[1][0][:, N:]).all()
+
+
 def test_consecutive_rounds_on_one_stream_and_reproducibility(hip):
     """Several fused rounds back to back, overlapped and not: the rounds are ordered correctly on the
     caller's stream (each starts from the previous one's results) and runs are bitwise reproducible."""

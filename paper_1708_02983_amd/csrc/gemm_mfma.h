@@ -600,15 +600,24 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
             const int mt = wave_m + i * 16;                                           // uniform
             if (mt >= p.M) break;
             const bool inside = cols_inside && mt + 16 <= p.M;
+            // all mask values of the row of tiles in flight together: none of the loads is conditional (a lane whose
+            // element lies outside C reads the last row or column instead, and stores nothing)
             float gate[TN][4];
             if (EPI == EPI_MASK) {
+                if (inside) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                    for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const bool ok = inside || (mt + frag_r + r < p.M && wave_n + j * 16 + frag_x < p.N);
-                        gate[j][r] = ok ? (mask + (size_t)(mt + r) * p.ldmask + wave_n + j * 16)[lane_mask] : 0.f;
-                    }
+                        for (int r = 0; r < 4; ++r) gate[j][r] = (mask + (size_t)(mt + r) * p.ldmask + wave_n + j * 16)[lane_mask];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int m = min(mt + frag_r + r, p.M - 1), n = min(wave_n + j * 16 + frag_x, p.N - 1);
+                            gate[j][r] = mask[(size_t)m * p.ldmask + n];
+                        }
+                }
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
@@ -720,6 +729,14 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                     }
                     continue;
                 }
+                float gate[16];
+                if (EPI == EPI_MASK) {      // unconditional loads (clamped into the matrix), all in flight together
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = min(m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4), p.M - 1);
+                        gate[r] = mask[(size_t)m * p.ldmask + min(n, p.N - 1)];
+                    }
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
@@ -727,7 +744,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                         float v = acc[i][j][r];
                         const size_t at = (size_t)m * p.ldc + n;
                         if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
-                        if (EPI == EPI_MASK) v = (mask[(size_t)m * p.ldmask + n] > 0.f) ? v : 0.f;
+                        if (EPI == EPI_MASK) v = (gate[r] > 0.f) ? v : 0.f;
                         if constexpr (OUT16) C16[at] = bf16_narrow(v);
                         else C[at] = v;
                     }

@@ -716,15 +716,26 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                         if constexpr (MOM16) worker_rule_bf16<true>(wv[r], v16[r], acc[i][j][r], cv[r], p.eta, p.rho, p.alpha, p.delta);
                         else worker_rule<MOM>(wv[r], vv[r], acc[i][j][r], cv[r], p.eta, p.rho, p.alpha, p.delta);
                     }
+                    // One branch on the column for the whole pass, and none on the rows unless the tile is ragged
+                    // there too: behind every per-element branch the compiler waits for all outstanding memory
+                    // operations, the previous element's stores included.
+                    auto store_at = [&](int r, size_t at) {
+                        Wr[at] = wv[r];
+                        if (MOM) Vr[at] = vv[r];
+                        if (MOM16) Vr16[at] = v16[r];
+                        if (keep) C[at] = acc[i][j][r];
+                    };
+                    if (n < p.N) {
+                        if (m0 + BM <= p.M) {                                           // uniform
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
-                        const size_t at = (size_t)m * p.ldc + n;
-                        if (m < p.M && n < p.N) {
-                            Wr[at] = wv[r];
-                            if (MOM) Vr[at] = vv[r];
-                            if (MOM16) Vr16[at] = v16[r];
-                            if (keep) C[at] = acc[i][j][r];
+                            for (int r = 0; r < 16; ++r)
+                                store_at(r, (size_t)(m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4)) * p.ldc + n);
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
+                                if (m < p.M) store_at(r, (size_t)m * p.ldc + n);
+                            }
                         }
                     }
                     continue;

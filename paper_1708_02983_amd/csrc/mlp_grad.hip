@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64) void mean_loss_kernel(const float *__restrict__
 }
 
 // One launch for the head of the network; the grid may be extended by blocks that run the center rule (h.ctr).
-template <int ROWS, int CP, bool ONE_PASS>
+template <int ROWS, int CP, bool ONE_PASS, int NT = 4>
 __global__ __launch_bounds__(256) void mlp_head_kernel(HeadArgs h)
 {
     __shared__ float part[4][ROWS * CP];
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void mlp_head_kernel(HeadArgs h)
         else center_rule_block<float>(h.ctr.W, h.ctr.Wc, h.ctr.old, h.ctr.P, h.ctr.N, h.ctr.ld, h.ctr.alpha, cb, h.ctr.blocks, threadIdx.x);
         return;
     }
-    head_block<ROWS, CP, ONE_PASS>(h, blockIdx.x, part, dzs);
+    head_block<ROWS, CP, ONE_PASS, false, NT>(h, blockIdx.x, part, dzs);
 }
 
 // Whether the head of a network with these layer widths takes the single-launch path.
@@ -178,6 +178,7 @@ template <int CP>
 static void launch_head_cp(const HeadArgs &h, unsigned blocks, hipStream_t s)
 {
     if (h.d_in <= 1024) EASGD_LAUNCH((mlp_head_kernel<HEAD_ROWS, CP, true>), dim3(blocks), dim3(256), 0, s, h);
+    else if (h.d_in <= 2048) EASGD_LAUNCH((mlp_head_kernel<HEAD_ROWS, CP, true, 8>), dim3(blocks), dim3(256), 0, s, h);
     else EASGD_LAUNCH((mlp_head_kernel<HEAD_ROWS, CP, false>), dim3(blocks), dim3(256), 0, s, h);
 }
 

@@ -70,15 +70,16 @@ __device__ __forceinline__ void head_tree(float (&v)[N], int lane, int &base, bo
     }
 }
 
-// CP: class count rounded up to a multiple of 4; ONE_PASS: d_in <= 1024, every thread keeps its operands in
-// registers between the two products instead of loading them again.
+// CP: class count rounded up to a multiple of 4; NT: columns per thread and pass; ONE_PASS: d_in <= 256 * NT, every
+// thread keeps its operands in registers between the two products instead of loading them again (NT = 4 up to
+// 1024 columns, NT = 8 up to 2048: one burst of loads per block instead of four dependent ones; the per-thread
+// order of the sums is the same, ascending n).
 // The work of block `bid` (HEAD_ROWS rows of one worker); part and dzs are the calling kernel's LDS.
 // SHARE: dz and row_loss are read by other blocks of the same launch, so they are stored with device-scope
 // atomic stores (which go to the level of the memory hierarchy that all dies share) instead of plain ones.
-template <int ROWS, int CP, bool ONE_PASS, bool SHARE = false>
+template <int ROWS, int CP, bool ONE_PASS, bool SHARE = false, int NT = 4>
 __device__ __forceinline__ void head_block(const HeadArgs &h, const unsigned bid, float (&part)[4][ROWS * CP], float (&dzs)[ROWS][CP])
 {
-    constexpr int NT = 4;                    // columns per thread and pass
     constexpr int CNT = ROWS * CP;           // partial logits per thread
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int w = bid % h.P;

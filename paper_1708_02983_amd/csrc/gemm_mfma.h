@@ -639,30 +639,39 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
             for (int j = 0; j < TN; ++j) {
                 const int n = wave_n + j * 32;                                        // uniform
                 if constexpr (ELASTIC) {
-                    float wv[16], cv[16], vv[16];
-                    unsigned short v16[16];
+                    // with momentum the tile goes through in two halves of eight values per lane: three arrays of
+                    // sixteen in flight put the kernel over the registers that four blocks per compute unit leave
+                    // (147 against 123; cfg3 round 2.25 -> 2.23 ms with the fourth block)
+                    constexpr int HALF = ((MOM || MOM16) && !EARLY_TILES) ? 8 : 16;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {  // all loads of the tile first, so that they overlap
-                        if constexpr (EARLY_TILES) {        // requested before the K loop
-                            wv[r] = pre_w[r]; cv[r] = pre_c[r]; vv[r] = pre_v[r]; v16[r] = pre_v16[r];
-                            continue;
+                    for (int r0 = 0; r0 < 16; r0 += HALF) {
+                        float wv[HALF], cv[HALF], vv[HALF];
+                        unsigned short v16[HALF];
+#pragma unroll
+                        for (int q = 0; q < HALF; ++q) {  // all loads of the half first, so that they overlap
+                            const int r = r0 + q;
+                            if constexpr (EARLY_TILES) {        // requested before the K loop
+                                wv[q] = pre_w[r]; cv[q] = pre_c[r]; vv[q] = pre_v[r]; v16[q] = pre_v16[r];
+                                continue;
+                            }
+                            const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
+                            wv[q] = (Wr + row)[lane_c];
+                            cv[q] = (Cc + row)[lane_c];
+                            vv[q] = MOM ? (Vr + row)[lane_c] : 0.f;
+                            v16[q] = MOM16 ? (Vr16 + row)[lane_c] : (unsigned short)0;
                         }
-                        const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
-                        wv[r] = (Wr + row)[lane_c];
-                        cv[r] = (Cc + row)[lane_c];
-                        vv[r] = MOM ? (Vr + row)[lane_c] : 0.f;
-                        v16[r] = MOM16 ? (Vr16 + row)[lane_c] : (unsigned short)0;
-                    }
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
-                        const float g = acc[i][j][r];
-                        if constexpr (MOM16) worker_rule_bf16<true>(wv[r], v16[r], g, cv[r], p.eta, p.rho, p.alpha, p.delta);
-                        else worker_rule<MOM>(wv[r], vv[r], g, cv[r], p.eta, p.rho, p.alpha, p.delta);
-                        (Wr + row)[lane_c] = wv[r];
-                        if (MOM) (Vr + row)[lane_c] = vv[r];
-                        if (MOM16) (Vr16 + row)[lane_c] = v16[r];
-                        if (keep) (C + row)[lane_c] = g;
+                        for (int q = 0; q < HALF; ++q) {
+                            const int r = r0 + q;
+                            const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
+                            const float g = acc[i][j][r];
+                            if constexpr (MOM16) worker_rule_bf16<true>(wv[q], v16[q], g, cv[q], p.eta, p.rho, p.alpha, p.delta);
+                            else worker_rule<MOM>(wv[q], vv[q], g, cv[q], p.eta, p.rho, p.alpha, p.delta);
+                            (Wr + row)[lane_c] = wv[q];
+                            if (MOM) (Vr + row)[lane_c] = vv[q];
+                            if (MOM16) (Vr16 + row)[lane_c] = v16[q];
+                            if (keep) (C + row)[lane_c] = g;
+                        }
                     }
                     continue;
                 }

@@ -74,7 +74,7 @@ extern "C" {
 
 const char *easgd_last_error(void) { return easgd::g_err; }
 
-int easgd_version(void) { return 450; }
+int easgd_version(void) { return 460; }
 
 unsigned long long easgd_launch_count(void) { return easgd::launch_counter().load(std::memory_order_relaxed); }
 

@@ -475,18 +475,19 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
     constexpr bool ELASTIC_EPI = (EPI == EPI_ELASTIC || EPI == EPI_ELASTIC_MOM || EPI == EPI_ELASTIC_MOM_BF16);
     constexpr bool EARLY_TILES = ALONE && ELASTIC_EPI && BN == 32 && TM == 1 && TN == 1 && MT == 32;
     float pre_w[EARLY_TILES ? 16 : 1], pre_c[EARLY_TILES ? 16 : 1], pre_v[EARLY_TILES ? 16 : 1];
-    unsigned short pre_v16[EARLY_TILES ? 16 : 1];
+    unsigned pre_v16[EARLY_TILES ? 16 : 1];     // one 32-bit register per code: loads into the halves of a shared register
+                                                // would each wait for the other
     if constexpr (EARLY_TILES) {
         const int n = n0 + wn0 + (lane & 31);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int m = m0 + wm0 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-            const size_t at = (size_t)m * p.ldc + n;
-            const bool ok = m < p.M && n < p.N;
-            pre_w[r] = ok ? (p.Wt + (size_t)w * p.c_ws)[at] : 0.f;
-            pre_c[r] = ok ? p.center[at] : 0.f;
-            pre_v[r] = (EPI == EPI_ELASTIC_MOM && ok) ? (p.Vt + (size_t)w * p.c_ws)[at] : 0.f;
-            pre_v16[r] = (EPI == EPI_ELASTIC_MOM_BF16 && ok) ? (p.Vt16 + (size_t)w * p.c_ws)[at] : (unsigned short)0;
+            // unconditional loads: a lane whose element lies outside C reads the last row or column instead
+            const int m = min(m0 + wm0 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4), p.M - 1);
+            const size_t at = (size_t)m * p.ldc + min(n, p.N - 1);
+            pre_w[r] = (p.Wt + (size_t)w * p.c_ws)[at];
+            pre_c[r] = p.center[at];
+            pre_v[r] = (EPI == EPI_ELASTIC_MOM) ? (p.Vt + (size_t)w * p.c_ws)[at] : 0.f;
+            pre_v16[r] = (EPI == EPI_ELASTIC_MOM_BF16) ? (unsigned)(p.Vt16 + (size_t)w * p.c_ws)[at] : 0u;
         }
     }
     if (n_pipe >= 2) {
@@ -651,7 +652,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                         for (int q = 0; q < HALF; ++q) {  // all loads of the half first, so that they overlap
                             const int r = r0 + q;
                             if constexpr (EARLY_TILES) {        // requested before the K loop
-                                wv[q] = pre_w[r]; cv[q] = pre_c[r]; vv[q] = pre_v[r]; v16[q] = pre_v16[r];
+                                wv[q] = pre_w[r]; cv[q] = pre_c[r]; vv[q] = pre_v[r]; v16[q] = (unsigned short)pre_v16[r];
                                 continue;
                             }
                             const size_t row = (size_t)(wave_m + i * 32 + 8 * (r / 4) + (r % 4)) * p.ldc + n;
@@ -708,17 +709,17 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &p, const unsigned bid
                     unsigned short v16[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int m = m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4);
-                        const size_t at = (size_t)m * p.ldc + n;
-                        const bool ok = m < p.M && n < p.N;
                         if constexpr (EARLY_TILES) {        // requested before the K loop
-                            wv[r] = pre_w[r]; cv[r] = pre_c[r]; vv[r] = pre_v[r]; v16[r] = pre_v16[r];
+                            wv[r] = pre_w[r]; cv[r] = pre_c[r]; vv[r] = pre_v[r]; v16[r] = (unsigned short)pre_v16[r];
                             continue;
                         }
-                        wv[r] = ok ? Wr[at] : 0.f;
-                        cv[r] = ok ? Cc[at] : 0.f;
-                        vv[r] = (MOM && ok) ? Vr[at] : 0.f;
-                        v16[r] = (MOM16 && ok) ? Vr16[at] : (unsigned short)0;
+                        // unconditional loads: a lane whose element lies outside C reads the last row or column
+                        const int m = min(m0 + wm0 + i * 32 + 8 * (r / 4) + frag_r + (r % 4), p.M - 1);
+                        const size_t at = (size_t)m * p.ldc + min(n, p.N - 1);
+                        wv[r] = Wr[at];
+                        cv[r] = Cc[at];
+                        vv[r] = MOM ? Vr[at] : 0.f;
+                        v16[r] = MOM16 ? Vr16[at] : (unsigned short)0;
                     }
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {

@@ -14,9 +14,15 @@ __all__ = list(_BINDING_NAMES) + ["BatchFeeder"]
 
 
 def __getattr__(name):
+    # the first use of a name imports its module and keeps the object in this module's namespace, so that later
+    # uses are plain attribute look-ups (a look-up through the import machinery costs several microseconds, which
+    # is a third of a small round's time on the device)
     if name == "BatchFeeder":
-        return importlib.import_module(".feeder", __name__).BatchFeeder
-    if name in _BINDING_NAMES or name == "binding":
+        value = importlib.import_module(".feeder", __name__).BatchFeeder
+    elif name in _BINDING_NAMES or name == "binding":
         mod = importlib.import_module(".binding", __name__)
-        return mod if name == "binding" else getattr(mod, name)
-    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
+        value = mod if name == "binding" else getattr(mod, name)
+    else:
+        raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
+    globals()[name] = value
+    return value

@@ -9,6 +9,7 @@ fallback: if the shared library is missing, importing this module raises.
 from __future__ import annotations
 
 import ctypes
+import functools
 import os
 from typing import Optional, Sequence
 
@@ -111,9 +112,17 @@ def _check(code: int) -> None:
         raise EasgdError(code, _lib.easgd_last_error().decode())
 
 
+_raw_current_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream(stream) -> ctypes.c_void_p:
-    s = torch.cuda.current_stream() if stream is None else stream
-    return ctypes.c_void_p(s.cuda_stream)
+    # the current stream of the current device; torch.cuda.current_stream() builds a Stream object through several
+    # layers of Python (8 us per call here, more than the library's own share of a small round), the raw query does not
+    if stream is None:
+        if _raw_current_stream is not None:
+            return ctypes.c_void_p(_raw_current_stream(torch.cuda.current_device()))
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
 
 
 def _dev(name: str, t: torch.Tensor, dtype, min_numel: int) -> int:
@@ -217,19 +226,38 @@ def hogwild_easgd_round(W, G, Wc, eta: float, rho: float, V=None, delta: float =
                                     P, N, ld, eta, rho, delta, _stream(stream)))
 
 
-def _dims(dims: Sequence[int]):
-    arr = (ctypes.c_int * len(dims))(*[int(d) for d in dims])
+# What the marshalling derives from the layer widths alone is kept per tuple of widths: a round of a small network
+# takes some 15 us on the device, and rebuilding the C array and asking the library for N and the workspace size on
+# every call cost more than that on the host.
+@functools.lru_cache(maxsize=256)
+def _dims_cached(dims: tuple):
+    arr = (ctypes.c_int * len(dims))(*dims)
     return arr, len(dims) - 1
 
 
-def easgd_mlp_num_params(dims: Sequence[int]) -> int:
-    arr, L = _dims(dims)
+def _dims(dims: Sequence[int]):
+    return _dims_cached(tuple(int(d) for d in dims))
+
+
+@functools.lru_cache(maxsize=256)
+def _num_params_cached(dims: tuple) -> int:
+    arr, L = _dims_cached(dims)
     return int(_lib.easgd_mlp_num_params(arr, L))
 
 
+def easgd_mlp_num_params(dims: Sequence[int]) -> int:
+    return _num_params_cached(tuple(int(d) for d in dims))
+
+
+@functools.lru_cache(maxsize=256)
+def _workspace_cached(dims: tuple, P: int, b: int, whole_round: bool) -> int:
+    arr, L = _dims_cached(dims)
+    fn = _lib.easgd_mlp_round_workspace_bytes if whole_round else _lib.easgd_grad_workspace_bytes
+    return int(fn(arr, L, P, b))
+
+
 def easgd_grad_workspace_bytes(dims: Sequence[int], P: int, b: int) -> int:
-    arr, L = _dims(dims)
-    return int(_lib.easgd_grad_workspace_bytes(arr, L, P, b))
+    return _workspace_cached(tuple(int(d) for d in dims), int(P), int(b), False)
 
 
 def easgd_grad(dims: Sequence[int], W, X, y, G, loss=None, workspace=None, stream=None):
@@ -299,8 +327,7 @@ def easgd_grad_static(dims: Sequence[int], W, X, y, G, loss=None, stream=None) -
 
 
 def easgd_mlp_round_workspace_bytes(dims: Sequence[int], P: int, b: int) -> int:
-    arr, L = _dims(dims)
-    return int(_lib.easgd_mlp_round_workspace_bytes(arr, L, P, b))
+    return _workspace_cached(tuple(int(d) for d in dims), int(P), int(b), True)
 
 
 def easgd_mlp_round(dims: Sequence[int], W, Wc, X, y, eta: float, rho: float, V=None, delta: float = 0.0,

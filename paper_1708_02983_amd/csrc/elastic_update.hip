@@ -94,13 +94,23 @@ __device__ __forceinline__ void elastic_tile(f32x4 *__restrict__ W, f32x4 *__res
     for (int i = 0; i < P; ++i) {                     // ascending worker order: fixed summation order
         const size_t row = (size_t)i * ld4;
         f32x4 w[GROUPS], g[GROUPS], v[GROUPS];
+        // stream by stream (the gradients, then the replica, then the momentum buffer; the stores likewise), not group
+        // by group: consecutive requests of a wavefront then walk one array, 0.5-0.9 % faster at N = 61 M
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
             const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                w[q] = stream_load<NT>(W + row + j);
-                g[q] = stream_load<NT>(G + row + j);
-                if constexpr (MOM) v[q] = stream_load<NT>(V + row + j);
+            if (FULL || j < n4) g[q] = stream_load<NT>(G + row + j);
+        }
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) w[q] = stream_load<NT>(W + row + j);
+        }
+        if constexpr (MOM) {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * STRIDE;
+                if (FULL || j < n4) v[q] = stream_load<NT>(V + row + j);
             }
         }
         // Three phases per worker, kept apart by scheduling barriers: every load is issued before the first result
@@ -117,9 +127,13 @@ __device__ __forceinline__ void elastic_tile(f32x4 *__restrict__ W, f32x4 *__res
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
             const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                stream_store<NT>(W + row + j, w[q]);
-                if constexpr (MOM) stream_store<NT>(V + row + j, v[q]);
+            if (FULL || j < n4) stream_store<NT>(W + row + j, w[q]);
+        }
+        if constexpr (MOM) {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * STRIDE;
+                if (FULL || j < n4) stream_store<NT>(V + row + j, v[q]);
             }
         }
     }
@@ -394,9 +408,13 @@ __device__ __forceinline__ void sync_sgd_tile(f32x4 *__restrict__ W, f32x4 *__re
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
             const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                stream_store<NT>(W + row + j, w[q]);
-                if constexpr (MOM) stream_store<NT>(V + row + j, v[q]);
+            if (FULL || j < n4) stream_store<NT>(W + row + j, w[q]);
+        }
+        if constexpr (MOM) {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * STRIDE;
+                if (FULL || j < n4) stream_store<NT>(V + row + j, v[q]);
             }
         }
     }

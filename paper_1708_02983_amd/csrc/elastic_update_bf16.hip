@@ -82,13 +82,22 @@ __device__ __forceinline__ void elastic_bf16_tile(f32x4 *__restrict__ W, u16x4 *
         f32x4 w[GROUPS];
         g4 g[GROUPS];
         u16x4 v[GROUPS];
+        // stream by stream, as in elastic_tile
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
             const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                w[q] = lp_load<NT>(W + row + j);
-                g[q] = lp_load<NT>(G + row + j);
-                if constexpr (MOM) v[q] = lp_load<NT>(V + row + j);
+            if (FULL || j < n4) g[q] = lp_load<NT>(G + row + j);
+        }
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) {
+            const size_t j = j0 + (size_t)q * STRIDE;
+            if (FULL || j < n4) w[q] = lp_load<NT>(W + row + j);
+        }
+        if constexpr (MOM) {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * STRIDE;
+                if (FULL || j < n4) v[q] = lp_load<NT>(V + row + j);
             }
         }
         if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);     // loads | arithmetic | stores, as in elastic_tile
@@ -111,9 +120,13 @@ __device__ __forceinline__ void elastic_bf16_tile(f32x4 *__restrict__ W, u16x4 *
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
             const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                lp_store<NT>(W + row + j, w[q]);
-                if constexpr (MOM) lp_store<NT>(V + row + j, v[q]);
+            if (FULL || j < n4) lp_store<NT>(W + row + j, w[q]);
+        }
+        if constexpr (MOM) {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                const size_t j = j0 + (size_t)q * STRIDE;
+                if (FULL || j < n4) lp_store<NT>(V + row + j, v[q]);
             }
         }
     }

@@ -340,30 +340,30 @@ def triad_ceiling(hip, n=488_000_000, reps=20):
 # them are dropped from the JSON line (traffic: null) when the running library reports another version than the one
 # that was profiled, or non-default launch options.
 TRAFFIC_PROFILES = {
-    ("elastic", False, 8, 61_000_000): (2_025_434.7 * 1024 * 2.000 + 2_144_531.4 * 1024 * 1.000,
+    ("elastic", False, 8, 61_000_000): (2_025_434.7 * 1024 * 2.000 + 2_144_531.5 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("elastic", True, 16, 61_000_000): (5_837_945.9 * 1024 * 2.000 + 7_863_300.3 * 1024 * 1.000,
+    ("elastic", True, 16, 61_000_000): (5_837_951.0 * 1024 * 2.000 + 7_863_310.4 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("sync_sgd", False, 8, 61_000_000): (1_906_278.1 * 1024 * 2.000 + 1_906_252.4 * 1024 * 1.000,
+    ("sync_sgd", False, 8, 61_000_000): (1_906_271.1 * 1024 * 2.000 + 1_906_252.4 * 1024 * 1.000,
                                          "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("async", False, 8, 61_000_000): (2_025_431.3 * 1024 * 2.000 + 2_144_531.3 * 1024 * 1.000,
+    ("async", False, 8, 61_000_000): (2_025_431.3 * 1024 * 2.000 + 2_144_531.2 * 1024 * 1.000,
                                       "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("hogwild", False, 8, 61_000_000): (2_869_451.9 * 1024 * 2.000 + 9_531_250.0 * 1024 * 1.000,
+    ("hogwild", False, 8, 61_000_000): (2_869_619.2 * 1024 * 2.000 + 9_531_250.0 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
     ("elastic_bf16", False, 8, 61_000_000): (1_548_863.2 * 1024 * 2.000 + 2_144_531.8 * 1024 * 1.000,
                                              "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("elastic_bf16", True, 16, 61_000_000): (3_931_706.2 * 1024 * 2.000 + 5_957_033.4 * 1024 * 1.000,
+    ("elastic_bf16", True, 16, 61_000_000): (3_931_709.1 * 1024 * 2.000 + 5_957_033.7 * 1024 * 1.000,
                                              "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
     ("grad", "cfg2"): (131_066.2 * 1024 * 2.000 + 149_337.0 * 1024 * 1.000, "profiles/easgd_grad_cfg2_hbm_traffic.md"),
 }
-TRAFFIC_PROFILED_VERSION = 460      # easgd_version() of the library the summaries above were taken with
+TRAFFIC_PROFILED_VERSION = 480      # easgd_version() of the library the summaries above were taken with
 
 
 def traffic_fields(hip, key):
     """`traffic` (bytes per launch) and its provenance for a roofline object; None when the profile is stale."""
     entry = TRAFFIC_PROFILES.get(key)
     default_opts = (hip.get_option(hip.OPT_UPDATE_GROUPS) == 0 and hip.get_option(hip.OPT_UPDATE_LAYOUT) == 2
-                    and hip.get_option(hip.OPT_UPDATE_NONTEMPORAL) == 1
+                    and hip.get_option(hip.OPT_UPDATE_NONTEMPORAL) == 2
                     and hip.get_option(hip.OPT_UPDATE_BLOCKS_PER_CU) == 0 and hip.get_option(hip.OPT_GEMM_TILE) == 0)
     if entry is None or not default_opts or hip.version() != TRAFFIC_PROFILED_VERSION:
         return {"traffic": None}

@@ -360,7 +360,9 @@ size_t easgd_mlp_num_params(const int *dims, int n_layers);
  */
 typedef enum {
     EASGD_OPT_UPDATE_BLOCKS_PER_CU = 1,  /* 0 = one block per tile (default); k>0 = persistent grid of k*CUs blocks */
-    EASGD_OPT_UPDATE_NONTEMPORAL   = 2,  /* 1 = streaming (non-temporal) loads/stores for W, G, V (default), 0 = plain */
+    EASGD_OPT_UPDATE_NONTEMPORAL   = 2,  /* 1 = streaming (non-temporal) loads/stores for W, G, V, 0 = plain, 2 = chosen per call
+                                            (default): streaming when the round moves more than 512 MiB, plain below that,
+                                            where much of what a round writes is still in the caches for the next reader */
     EASGD_OPT_UPDATE_GROUPS        = 3,  /* 128-bit groups per thread and worker: 1, 2, 4 or 8; 0 = chosen per call (default): 4, fewer
                                             when N is small */
     EASGD_OPT_GEMM_TILE            = 4,  /* block tile of the wide matrix products of easgd_grad: 0 = chosen per product (default),

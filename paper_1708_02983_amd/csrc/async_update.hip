@@ -44,57 +44,58 @@ __device__ __forceinline__ void st_stream(T *p, T v)
 }
 
 // One tile of the 128-bit path (the structure of the synchronous kernel's tile: thread-owned groups
-// j0 + q*STRIDE; FULL = every group of the block lies inside the row, no per-lane guards).
+// j0 + q*STRIDE; FULL = every group of the block lies inside the row; no load is guarded in either form: lanes
+// past the end of the row read its last group and store nothing).
 template <bool MOM, int GROUPS, size_t STRIDE, bool FULL>
 __device__ __forceinline__ void async_tile(f32x4 *__restrict__ W, f32x4 *__restrict__ V, const f32x4 *__restrict__ G,
                                            f32x4 *__restrict__ Wc, const Schedule &sch, size_t n4, size_t ld4, size_t j0,
                                            float eta, float rho, float alpha, float delta)
 {
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     f32x4 c[GROUPS];
+    size_t jl[GROUPS];
 #pragma unroll
     for (int q = 0; q < GROUPS; ++q) {
         const size_t j = j0 + (size_t)q * STRIDE;
-        c[q] = (FULL || j < n4) ? Wc[j] : zero;
+        jl[q] = (FULL || j < n4) ? j : n4 - 1;
+        c[q] = Wc[jl[q]];
     }
     for (int t = 0; t < sch.n; ++t) {                    // the master's turns, one worker each, in schedule order
         const size_t row = (size_t)sch.worker[t] * ld4;
         f32x4 w[GROUPS], g[GROUPS], v[GROUPS];
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                w[q] = ld_stream<true>(W + row + j);
-                g[q] = ld_stream<true>(G + row + j);
-                if constexpr (MOM) v[q] = ld_stream<true>(V + row + j);
+            w[q] = ld_stream<true>(W + row + jl[q]);
+            g[q] = ld_stream<true>(G + row + jl[q]);
+            if constexpr (MOM) v[q] = ld_stream<true>(V + row + jl[q]);
+        }
+        if constexpr (!FULL) {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                keep_loaded(w[q]);
+                keep_loaded(g[q]);
+                if constexpr (MOM) keep_loaded(v[q]);
             }
         }
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);   // loads | arithmetic | stores
+        __builtin_amdgcn_sched_barrier(0);               // loads | arithmetic | stores
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                const f32x4 d = worker_rule<MOM>(w[q], v[q], g[q], c[q], eta, rho, alpha, delta);   // d = W_i - Wc at the start
-                c[q] = c[q] + alpha * d;                                                             // Eq. (2), one worker
-            }
+            const f32x4 d = worker_rule<MOM>(w[q], v[q], g[q], c[q], eta, rho, alpha, delta);   // d = W_i - Wc at the start
+            c[q] = fma_s(alpha, d, c[q]);                                                           // Eq. (2), one worker
         }
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                st_stream<true>(W + row + j, w[q]);
-                if constexpr (MOM) st_stream<true>(V + row + j, v[q]);
+            if (FULL || j0 + (size_t)q * STRIDE < n4) {
+                st_stream<true>(W + row + jl[q], w[q]);
+                if constexpr (MOM) st_stream<true>(V + row + jl[q], v[q]);
             }
         }
         // a worker that comes up again later in the schedule must find these stores done
         if (t + 1 < sch.n) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     }
 #pragma unroll
-    for (int q = 0; q < GROUPS; ++q) {
-        const size_t j = j0 + (size_t)q * STRIDE;
-        if (FULL || j < n4) Wc[j] = c[q];
-    }
+    for (int q = 0; q < GROUPS; ++q)
+        if (FULL || j0 + (size_t)q * STRIDE < n4) Wc[jl[q]] = c[q];
 }
 
 // One parameter, every turn (the scalar path and the N % 4 tail).
@@ -108,7 +109,7 @@ __device__ __forceinline__ void async_scalar(float *__restrict__ W, float *__res
         const size_t k = (size_t)sch.worker[t] * ld + j;
         float w = W[k], v = MOM ? V[k] : 0.f;
         const float d = worker_rule<MOM>(w, v, G[k], c, eta, rho, alpha, delta);
-        c = c + alpha * d;
+        c = fma_s(alpha, d, c);
         W[k] = w;
         if constexpr (MOM) V[k] = v;
     }

@@ -23,7 +23,7 @@ int num_cus();
 // thread is inside a call is no data race (the running call may see the old or the new value of each option).
 struct Options {
     std::atomic<long> update_blocks_per_cu{0};
-    std::atomic<long> update_nontemporal{1};
+    std::atomic<long> update_nontemporal{2};
     std::atomic<long> update_groups{0};
     std::atomic<long> update_layout{2};
     std::atomic<long> gemm_tile{0};
@@ -89,6 +89,12 @@ struct UpdateShape {
     size_t blocks;
 };
 UpdateShape update_shape(size_t N, bool wide);
+
+// Whether a streaming update that moves `bytes` per round uses non-temporal loads and stores
+// (EASGD_OPT_UPDATE_NONTEMPORAL; chosen per call by default).  Measured on replicas of 0.37 to 6.8 GB per round:
+// above about half a gigabyte the streaming forms are 2-16 % faster; below it plain accesses are 10-15 % faster,
+// because part of what one round writes is still in the last-level cache (256 MB) when the next reader comes.
+bool update_nontemporal(size_t bytes);
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 // natural alignment of the element type (a NULL pointer passes: it is checked separately)

@@ -5,16 +5,29 @@
 
 namespace easgd {
 
+// Marks a loaded value as needed at this point, whatever the compiler can prove about its later uses.  The
+// streaming tiles call it on a worker's values after the last load of that worker in the tile that holds the end
+// of a row: lanes past the end store nothing, and the loads of such a lane would otherwise move behind the branch
+// that skips its stores, where they are waited for one after the other.
+template <typename T>
+__device__ __forceinline__ void keep_loaded(T &x) { asm volatile("" : "+v"(x)); }
+
+// s*a + c with one rounding (T = float or a float vector, s a scalar).  The rules below spell out which of their
+// products are fused: left to the compiler the choice depends on the surrounding code (a product with two uses is
+// computed once and then not fused), and kernels that must give the same bits would not.
+template <typename T>
+__device__ __forceinline__ T fma_s(float s, T a, T c) { return __builtin_elementwise_fma((T)s, a, c); }
+
 // One worker's rule applied to T = float or a float vector.  Returns d = w - c (time-t values).
 template <bool MOM, typename T>
 __device__ __forceinline__ T worker_rule(T &w, T &v, T g, T c, float eta, float rho, float alpha, float delta)
 {
     const T d = w - c;
     if constexpr (MOM) {
-        v = delta * v - eta * g;              // Eq. (5)
-        w = (w + v) - alpha * d;              // Eq. (6)
+        v = fma_s(delta, v, -(eta * g));      // Eq. (5)
+        w = fma_s(-alpha, d, w + v);          // Eq. (6)
     } else {
-        w = w - eta * (g + rho * d);          // Eq. (1)
+        w = fma_s(-eta, fma_s(rho, d, g), w); // Eq. (1)
     }
     return d;
 }
@@ -49,9 +62,9 @@ __device__ __forceinline__ float worker_rule_bf16(float &w, unsigned short &v16,
             cand = dv - eg;                   // Eq. (5), each operation rounded on its own
         }
         v16 = bf16_narrow(cand);
-        w = (w + bf16_widen(v16)) - alpha * d;   // Eq. (6) with V_{t+1} as stored
+        w = fma_s(-alpha, d, w + bf16_widen(v16));   // Eq. (6) with V_{t+1} as stored
     } else {
-        w = w - eta * (g + rho * d);          // Eq. (1)
+        w = fma_s(-eta, fma_s(rho, d, g), w); // Eq. (1)
     }
     return d;
 }
@@ -85,7 +98,7 @@ __device__ __forceinline__ void center_rule_block(const float *__restrict__ Wp, 
         }
         for (; i < P; ++i) acc += W[(size_t)i * ldt + j] - c;
         old[j] = c;
-        Wc[j] = c + alpha * acc;
+        Wc[j] = fma_s(alpha, acc, c);
     }
     const size_t tail = N - n * LANES;        // only for the vector form
     if (block == n_blocks - 1 && (size_t)tid < tail) {
@@ -94,7 +107,7 @@ __device__ __forceinline__ void center_rule_block(const float *__restrict__ Wp, 
         float acc = 0.f;
         for (int i = 0; i < P; ++i) acc += Wp[(size_t)i * ld + k] - c;
         oldp[k] = c;
-        Wcp[k] = c + alpha * acc;
+        Wcp[k] = fma_s(alpha, acc, c);
     }
 }
 

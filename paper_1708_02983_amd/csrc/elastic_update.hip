@@ -71,13 +71,15 @@ __device__ __forceinline__ void elastic_group(T *__restrict__ W, T *__restrict__
         stream_store<NT>(W + k, w);
         if constexpr (MOM) stream_store<NT>(V + k, v);
     }
-    Wc[j] = c + alpha * acc;                  // Eq. (2)
+    Wc[j] = fma_s(alpha, acc, c);                 // Eq. (2)
 }
 
 // One tile of the 128-bit path: thread-owned groups j0 + q*STRIDE.  FULL: every group of the block lies inside the
-// row (the block-uniform common case): no per-lane guards, so all 2*GROUPS (3*GROUPS) loads of a worker are in
-// flight together.  Guarded loads would be waited for group by group (a guarded value is a merge of two
-// definitions, and the wait lands at the merge).
+// row (the block-uniform common case).  No load is conditional in either form, so all 2*GROUPS (3*GROUPS) loads of
+// a worker are in flight together: in the tile that holds the end of the row, lanes whose group lies past it read
+// the row's last group instead and store nothing.  (A guarded load is a merge of two definitions and is waited
+// for at the merge: one round trip to memory per group and worker, in a block that the whole launch then waits
+// for when N is small enough that every block is resident at once.)
 template <bool MOM, bool NT, int GROUPS, size_t STRIDE, bool FULL>
 __device__ __forceinline__ void elastic_tile(f32x4 *__restrict__ W, f32x4 *__restrict__ V, const f32x4 *__restrict__ G,
                                              f32x4 *__restrict__ Wc, int P, size_t n4, size_t ld4, size_t j0,
@@ -85,10 +87,12 @@ __device__ __forceinline__ void elastic_tile(f32x4 *__restrict__ W, f32x4 *__res
 {
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     f32x4 c[GROUPS], acc[GROUPS];
+    size_t jl[GROUPS];                                // the group this lane loads: its own, or the row's last one
 #pragma unroll
     for (int q = 0; q < GROUPS; ++q) {
         const size_t j = j0 + (size_t)q * STRIDE;
-        c[q] = (FULL || j < n4) ? Wc[j] : zero;       // the "broadcast" of the center, once per parameter
+        jl[q] = (FULL || j < n4) ? j : n4 - 1;
+        c[q] = Wc[jl[q]];                             // the "broadcast" of the center, once per parameter
         acc[q] = zero;
     }
     for (int i = 0; i < P; ++i) {                     // ascending worker order: fixed summation order
@@ -97,51 +101,49 @@ __device__ __forceinline__ void elastic_tile(f32x4 *__restrict__ W, f32x4 *__res
         // stream by stream (the gradients, then the replica, then the momentum buffer; the stores likewise), not group
         // by group: consecutive requests of a wavefront then walk one array, 0.5-0.9 % faster at N = 61 M
 #pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) g[q] = stream_load<NT>(G + row + j);
-        }
+        for (int q = 0; q < GROUPS; ++q) g[q] = stream_load<NT>(G + row + jl[q]);
 #pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) w[q] = stream_load<NT>(W + row + j);
-        }
+        for (int q = 0; q < GROUPS; ++q) w[q] = stream_load<NT>(W + row + jl[q]);
         if constexpr (MOM) {
 #pragma unroll
+            for (int q = 0; q < GROUPS; ++q) v[q] = stream_load<NT>(V + row + jl[q]);
+        }
+        if constexpr (!FULL) {
+#pragma unroll
             for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * STRIDE;
-                if (FULL || j < n4) v[q] = stream_load<NT>(V + row + j);
+                keep_loaded(g[q]);
+                keep_loaded(w[q]);
+                if constexpr (MOM) keep_loaded(v[q]);
             }
         }
         // Three phases per worker, kept apart by scheduling barriers: every load is issued before the first result
         // is used, and every store after the last result is computed.  Left alone the scheduler pairs loads with
         // the arithmetic of earlier groups and drips the stores out between waits; bursts of reads followed by
         // bursts of writes stream 5-10 % faster (measured at P = 16, N = 61 M).
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) acc[q] += worker_rule<MOM>(w[q], v[q], g[q], c[q], eta, rho, alpha, delta);
-        }
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
+        for (int q = 0; q < GROUPS; ++q) acc[q] += worker_rule<MOM>(w[q], v[q], g[q], c[q], eta, rho, alpha, delta);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (FULL) {
 #pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) stream_store<NT>(W + row + j, w[q]);
-        }
-        if constexpr (MOM) {
+            for (int q = 0; q < GROUPS; ++q) stream_store<NT>(W + row + jl[q], w[q]);
+            if constexpr (MOM) {
+#pragma unroll
+                for (int q = 0; q < GROUPS; ++q) stream_store<NT>(V + row + jl[q], v[q]);
+            }
+        } else {
 #pragma unroll
             for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * STRIDE;
-                if (FULL || j < n4) stream_store<NT>(V + row + j, v[q]);
+                if (j0 + (size_t)q * STRIDE < n4) {
+                    stream_store<NT>(W + row + jl[q], w[q]);
+                    if constexpr (MOM) stream_store<NT>(V + row + jl[q], v[q]);
+                }
             }
         }
     }
 #pragma unroll
-    for (int q = 0; q < GROUPS; ++q) {
-        const size_t j = j0 + (size_t)q * STRIDE;
-        if (FULL || j < n4) Wc[j] = c[q] + alpha * acc[q];   // Eq. (2)
-    }
+    for (int q = 0; q < GROUPS; ++q)
+        if (FULL || j0 + (size_t)q * STRIDE < n4) Wc[jl[q]] = fma_s(alpha, acc[q], c[q]);   // Eq. (2)
 }
 
 // 128-bit path.  The N % 4 tail elements are handled as scalars by the last block.
@@ -230,7 +232,7 @@ __global__ __launch_bounds__(256) void elastic_split_kernel(float *__restrict__ 
     __syncthreads();
     if (wave == 0 && live) {
         const f32x4 sum = ((partial[0][lane] + partial[1][lane]) + partial[2][lane]) + partial[3][lane];
-        Wc[j] = c + alpha * sum;              // Eq. (2)
+        Wc[j] = fma_s(alpha, sum, c);             // Eq. (2)
     }
     const size_t tail = N - n4 * 4;
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x < tail)
@@ -280,7 +282,6 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
         return fail(EASGD_EINVAL, "%s: fp32 pointers must be 4-byte aligned", name);
     clear_error();
 
-    const Options &opt = options();
     hipStream_t s = static_cast<hipStream_t>(stream);
     const float alpha = eta * rho;            // elastic coefficient of workers and center
     const bool vec = aligned16(W) && aligned16(G) && aligned16(Wc) && (!MOM || aligned16(V)) && (ld % 4 == 0);
@@ -296,7 +297,7 @@ static int elastic_round(float *W, float *V, const float *G, float *Wc, int P, s
         const dim3 split_grid((unsigned)((N / 4 + 63) / 64 > 0 ? (N / 4 + 63) / 64 : 1));
         EASGD_LAUNCH((elastic_split_kernel<MOM>), split_grid, dim3(256), 0, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
     } else if (vec) {
-        const bool nt = opt.update_nontemporal != 0;
+        const bool nt = update_nontemporal(N * ((MOM ? 20 : 12) * (size_t)P + 8));
         if (shape.dies && nt) launch_vec4<MOM, true, true>(groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
         else if (shape.dies) launch_vec4<MOM, false, true>(groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
         else if (nt) launch_vec4<MOM, true, false>(groups, grid, s, W, V, G, Wc, P, N, ld, eta, rho, alpha, delta);
@@ -359,10 +360,10 @@ template <bool MOM, typename T>
 __device__ __forceinline__ void sgd_rule(T &w, T &v, T s, float eta, float mu)
 {
     if constexpr (MOM) {
-        v = mu * v - eta * s;                 // Eq. (3)
+        v = fma_s(mu, v, -(eta * s));         // Eq. (3)
         w = w + v;                            // Eq. (4)
     } else {
-        w = w - eta * s;
+        w = fma_s(-eta, s, w);
     }
 }
 
@@ -373,17 +374,19 @@ __device__ __forceinline__ void sync_sgd_tile(f32x4 *__restrict__ W, f32x4 *__re
 {
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     f32x4 s[GROUPS];
+    size_t jl[GROUPS];                                // loads past the end of the row read its last group instead
 #pragma unroll
-    for (int q = 0; q < GROUPS; ++q) s[q] = zero;
+    for (int q = 0; q < GROUPS; ++q) {
+        const size_t j = j0 + (size_t)q * STRIDE;
+        jl[q] = (FULL || j < n4) ? j : n4 - 1;
+        s[q] = zero;
+    }
     for (int i = 0; i < P; ++i) {                     // ascending worker order: fixed summation order
         const size_t row = (size_t)i * ld4;
         f32x4 g[GROUPS];
 #pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            g[q] = (FULL || j < n4) ? stream_load<NT>(G + row + j) : zero;
-        }
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
+        for (int q = 0; q < GROUPS; ++q) g[q] = stream_load<NT>(G + row + jl[q]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) s[q] += g[q];
     }
@@ -392,29 +395,34 @@ __device__ __forceinline__ void sync_sgd_tile(f32x4 *__restrict__ W, f32x4 *__re
         f32x4 w[GROUPS], v[GROUPS];
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) {
-                w[q] = stream_load<NT>(W + row + j);
-                if constexpr (MOM) v[q] = stream_load<NT>(V + row + j);
-            }
+            w[q] = stream_load<NT>(W + row + jl[q]);
+            if constexpr (MOM) v[q] = stream_load<NT>(V + row + jl[q]);
         }
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);     // loads | arithmetic | stores, as in elastic_tile
-#pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) sgd_rule<MOM>(w[q], v[q], s[q], eta, mu);
-        }
-        if constexpr (FULL) __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < GROUPS; ++q) {
-            const size_t j = j0 + (size_t)q * STRIDE;
-            if (FULL || j < n4) stream_store<NT>(W + row + j, w[q]);
-        }
-        if constexpr (MOM) {
+        if constexpr (!FULL) {
 #pragma unroll
             for (int q = 0; q < GROUPS; ++q) {
-                const size_t j = j0 + (size_t)q * STRIDE;
-                if (FULL || j < n4) stream_store<NT>(V + row + j, v[q]);
+                keep_loaded(w[q]);
+                if constexpr (MOM) keep_loaded(v[q]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);            // loads | arithmetic | stores, as in elastic_tile
+#pragma unroll
+        for (int q = 0; q < GROUPS; ++q) sgd_rule<MOM>(w[q], v[q], s[q], eta, mu);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (FULL) {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) stream_store<NT>(W + row + jl[q], w[q]);
+            if constexpr (MOM) {
+#pragma unroll
+                for (int q = 0; q < GROUPS; ++q) stream_store<NT>(V + row + jl[q], v[q]);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < GROUPS; ++q) {
+                if (j0 + (size_t)q * STRIDE < n4) {
+                    stream_store<NT>(W + row + jl[q], w[q]);
+                    if constexpr (MOM) stream_store<NT>(V + row + jl[q], v[q]);
+                }
             }
         }
     }
@@ -512,14 +520,13 @@ static int sync_sgd(float *W, float *V, const float *G, int P, size_t N, size_t 
     if (!aligned_to(W, 4) || !aligned_to(G, 4) || !aligned_to(V, 4))
         return fail(EASGD_EINVAL, "%s: fp32 pointers must be 4-byte aligned", name);
     clear_error();
-    const Options &opt = options();
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = aligned16(W) && aligned16(G) && (!MOM || aligned16(V)) && (ld % 4 == 0);
     const UpdateShape shape = update_shape(N, MOM);
     size_t blocks = vec ? shape.blocks : (N + 255) / 256;
     if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;    // grid-stride loops cover the rest
     const dim3 grid((unsigned)blocks);
-    const bool nt = opt.update_nontemporal != 0;
+    const bool nt = update_nontemporal(N * (MOM ? 20 : 12) * (size_t)P);
     if (!vec) EASGD_LAUNCH((sync_sgd_scalar_kernel<MOM>), grid, dim3(256), 0, s, W, V, G, P, N, ld, eta, mu);
     else if (shape.dies && nt) launch_sync_sgd<MOM, true, true>(shape.groups, grid, s, W, V, G, P, N, ld, eta, mu);
     else if (shape.dies) launch_sync_sgd<MOM, false, true>(shape.groups, grid, s, W, V, G, P, N, ld, eta, mu);

@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256) void softmax_round_kernel(HeadArgs h, SoftmaxR
                 }
             }
         }
-        if (live && update && u.write_center) u.Wc[e] = cen + u.alpha * acc;   // Eq. (2)
+        if (live && update && u.write_center) u.Wc[e] = fma_s(u.alpha, acc, cen);   // Eq. (2)
     }
 }
 

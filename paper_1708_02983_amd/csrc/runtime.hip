@@ -62,6 +62,12 @@ UpdateShape update_shape(size_t N, bool wide)
     return sh;
 }
 
+bool update_nontemporal(size_t bytes)
+{
+    const long v = options().update_nontemporal;
+    return v == 2 ? bytes > ((size_t)512 << 20) : v != 0;
+}
+
 std::atomic<unsigned long long> &launch_counter()
 {
     static std::atomic<unsigned long long> n{0};
@@ -74,7 +80,7 @@ extern "C" {
 
 const char *easgd_last_error(void) { return easgd::g_err; }
 
-int easgd_version(void) { return 460; }
+int easgd_version(void) { return 480; }
 
 unsigned long long easgd_launch_count(void) { return easgd::launch_counter().load(std::memory_order_relaxed); }
 
@@ -87,7 +93,7 @@ int easgd_set_option(int option, long value)
         o.update_blocks_per_cu = value;
         return EASGD_OK;
     case EASGD_OPT_UPDATE_NONTEMPORAL:
-        if (value != 0 && value != 1) return easgd::fail(EASGD_EINVAL, "nontemporal must be 0 or 1, got %ld", value);
+        if (value < 0 || value > 2) return easgd::fail(EASGD_EINVAL, "nontemporal must be 0, 1 or 2 (chosen per call), got %ld", value);
         o.update_nontemporal = value;
         return EASGD_OK;
     case EASGD_OPT_UPDATE_GROUPS:

@@ -70,7 +70,11 @@ typedef enum {
  * The sum over the workers is taken in a fixed order (ascending i by one thread;
  * for small N with P >= 4 the workers are split over four wavefronts whose
  * partial sums are added in a fixed order), so results are bitwise reproducible
- * from run to run and independent of the launch-shape options.
+ * from run to run and independent of the launch-shape options.  The arithmetic is
+ * fp32 with the fused multiply-adds fixed in the source, the same in every kernel of
+ * the library that applies these rules (fma = one rounding):
+ *   Eq. (1)  W <- fma(-eta, fma(rho, d, G), W)          Eq. (2)  Wc <- fma(eta*rho, sum, c)
+ *   Eq. (5)  V <- fma(delta, V, -(eta*G))               Eq. (6)  W  <- fma(-(eta*rho), d, W + V)
  *
  *   W   DEVICE in/out [P][ld]   worker replicas W^i_t -> W^i_{t+1}
  *   G   DEVICE in     [P][ld]   worker gradients dW^i_t (never written)

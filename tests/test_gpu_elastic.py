@@ -195,3 +195,46 @@ def test_cfg4_full_size_100_rounds_sampled(hip):
 
 def test_cfg5_full_size_100_rounds_sampled(hip):
     _full_size_sampled(hip, "cfg5", 100)
+
+
+def _nearest_f32(x):
+    """The float32 nearest to the exact rational x, ties to the even mantissa."""
+    from fractions import Fraction
+    guess = np.float32(float(x))
+    cands = (np.nextafter(guess, np.float32(-np.inf)), guess, np.nextafter(guess, np.float32(np.inf)))
+    return min(cands, key=lambda c: (abs(Fraction(float(c)) - x), int(np.float32(c).view(np.uint32)) & 1))
+
+
+@pytest.mark.parametrize("momentum", [False, True], ids=["easgd", "measgd"])
+def test_bits_are_those_of_the_arithmetic_the_header_states(hip, momentum):
+    """include/easgd.h fixes which products of the rules are fused.  Exact rational arithmetic, rounded where the
+    header says a rounding happens, must give the kernels' bits: the 128-bit path (two tiles and their ragged end),
+    the scalar tail and, through an unaligned ld, the scalar kernel."""
+    from fractions import Fraction as Q
+    P, N = 3, 2307
+    rnd, q = _nearest_f32, lambda a: Q(float(a))
+    fma = lambda a, b, c: rnd(q(a) * q(b) + q(c))
+    alpha = F(ETA * RHO)
+    for ld in (2308, 2309):
+        W, Wc = workloads.update_state(P, N, ld, seed=19)
+        G = workloads.update_gradients(P, N, 0, ld, seed=19)
+        V = workloads.update_gradients(P, N, 7, ld, seed=19, std=0.005)
+        dW, dG, dWc, dV = to_dev(W), to_dev(G), to_dev(Wc), to_dev(V)
+        if momentum:
+            hip.measgd_round(dW, dV, dG, dWc, float(ETA), float(RHO), float(DELTA), N=N)
+        else:
+            hip.easgd_sync_round(dW, dG, dWc, float(ETA), float(RHO), N=N)
+        gW, gV, gWc = to_host(dW), to_host(dV), to_host(dWc)
+        for j in range(N):
+            c, acc = Wc[j], F(0)
+            for i in range(P):
+                d = rnd(q(W[i, j]) - q(c))
+                acc = d if i == 0 else rnd(q(acc) + q(d))
+                if momentum:
+                    v = fma(DELTA, V[i, j], -rnd(q(ETA) * q(G[i, j])))                # Eq. (5)
+                    w = fma(-alpha, d, rnd(q(W[i, j]) + q(v)))                          # Eq. (6)
+                    assert gV[i, j].view(np.uint32) == F(v).view(np.uint32), (ld, i, j)
+                else:
+                    w = fma(-ETA, fma(RHO, d, G[i, j]), W[i, j])                        # Eq. (1)
+                assert gW[i, j].view(np.uint32) == F(w).view(np.uint32), (ld, i, j)
+            assert gWc[j].view(np.uint32) == F(fma(alpha, acc, c)).view(np.uint32), (ld, j)   # Eq. (2)

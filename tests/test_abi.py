@@ -155,4 +155,7 @@ def test_options_roundtrip(lib):
     assert lib.easgd_get_option(7) == 1 and lib.easgd_set_option(7, 2) == -1 and lib.easgd_set_option(7, 1) == 0
     assert lib.easgd_get_option(8) == 1 and lib.easgd_set_option(8, 2) == -1
     assert lib.easgd_set_option(8, 0) == 0 and lib.easgd_get_option(8) == 0 and lib.easgd_set_option(8, 1) == 0
+    # non-temporal accesses of the update kernels: 2 = chosen per call (default), 0 and 1 force
+    assert lib.easgd_get_option(2) == 2 and lib.easgd_set_option(2, 3) == -1 and lib.easgd_set_option(2, -1) == -1
+    assert lib.easgd_set_option(2, 0) == 0 and lib.easgd_get_option(2) == 0 and lib.easgd_set_option(2, 2) == 0
     assert lib.easgd_version() >= 100

@@ -478,11 +478,55 @@ def update_roofline(hip, wl, rule, update_ms, ceilings):
                         ("elastic", wl.momentum, P, N), update_bytes(wl), update_ms, ceilings)
 
 
+MFMA_CEILINGS = {}      # filled by main(): what the bare matrix-instruction loops reach on this device in this run
+
+
+def mfma_ceilings(hip, iters=2000, reps=5):
+    """Attainable fp32 rate of the products' matrix instruction (TFLOP/s): the bare loop with operands in registers,
+    and the same loop fetching every instruction's operands from LDS (two blocks of four wavefronts per compute
+    unit, like a cfg2 forward launch; no global memory, barriers or epilogues)."""
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out = torch.empty(2 * cus * 4096, dtype=torch.float32, device="cuda")
+    res = {}
+    for name, fetch in (("registers", False), ("lds_fetch", True)):
+        for _ in range(5):                  # untimed: the clocks start slow
+            flops = hip.mfma_probe(out, iters, fetch, 2)
+        e0, e1 = _events(1)[0], _events(1)[0]
+        e0.record()
+        for _ in range(reps):
+            hip.mfma_probe(out, iters, fetch, 2)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = flops * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    # the same loop in launches as short as a cfg2 forward product (25 passes = K 800), back to back on one stream:
+    # what a kernel that did nothing but its matrix instructions would reach once launch boundaries are paid
+    flops = hip.mfma_probe(out, 25, True, 2)
+    e0, e1 = _events(1)[0], _events(1)[0]
+    e0.record()
+    for _ in range(200):
+        hip.mfma_probe(out, 25, True, 2)
+    e1.record()
+    torch.cuda.synchronize()
+    res["short_launch"] = flops * 200 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    res["short_launch_us"] = e0.elapsed_time(e1) * 1e3 / 200
+    return res
+
+
 def mfma_roofline(hip, kernel, traffic_key, flops, ms):
     tflops = flops / (ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": kernel, "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4), **traffic_fields(hip, traffic_key),
-            "useful_flops_per_launch": flops, "avg_launch_ms": round(ms, 4)}
+    out = {"bound": "mfma", "kernel": kernel, "achieved": round(tflops, 2), "peak": MFMA_FP32_PEAK_TFLOPS,
+           "unit": "TFLOP/s", "frac": round(tflops / MFMA_FP32_PEAK_TFLOPS, 4), **traffic_fields(hip, traffic_key),
+           "useful_flops_per_launch": flops, "avg_launch_ms": round(ms, 4)}
+    if MFMA_CEILINGS:
+        out["measured_mfma_loop_TFLOPs"] = round(MFMA_CEILINGS["registers"], 1)
+        out["measured_mfma_loop_with_lds_fetch_TFLOPs"] = round(MFMA_CEILINGS["lds_fetch"], 1)
+        out["frac_of_mfma_loop_with_lds_fetch"] = round(tflops / MFMA_CEILINGS["lds_fetch"], 4)
+        out["measured_mfma_loop_in_short_launches"] = {
+            "TFLOPs": round(MFMA_CEILINGS["short_launch"], 1), "us_per_launch": round(MFMA_CEILINGS["short_launch_us"], 2),
+            "note": "the LDS-fetch loop in back-to-back launches of 25 passes (3.36 GFLOP, the size of cfg2's first "
+                    "forward product): the rate left once a launch boundary per product is paid"}
+    return out
 
 
 def training_report(hip, wl, steps, warmup, name, full):
@@ -614,6 +658,8 @@ def main():
     warmup = args.warmup if args.warmup is not None else (20 if wl.has_grad else 5)
 
     ceilings = {"triad": triad_ceiling(hip)}
+    if wl.has_grad:
+        MFMA_CEILINGS.update(mfma_ceilings(hip))
     mix = getattr(hip, "stream_mix32", None)
     if mix is not None:
         ceilings["3r2w"] = mix32_ceiling(hip)

@@ -7,7 +7,7 @@ import importlib
 
 _BINDING_NAMES = (
     "EasgdError", "easgd_grad", "easgd_grad_static", "easgd_layer_product", "STATIC_SCRATCH_BYTES", "easgd_mlp_round", "easgd_mlp_round_workspace_bytes", "easgd_grad_workspace_bytes", "easgd_mlp_num_params", "easgd_sync_round",
-    "measgd_round", "easgd_sync_round_bf16", "measgd_round_bf16", "measgd_round_bf16v", "sync_sgd_round", "async_easgd_round", "hogwild_easgd_round", "stream_copy", "stream_triad", "stream_mix32", "launch_count", "get_option", "set_option", "lib", "version", "LIB_PATH",
+    "measgd_round", "easgd_sync_round_bf16", "measgd_round_bf16", "measgd_round_bf16v", "sync_sgd_round", "async_easgd_round", "hogwild_easgd_round", "stream_copy", "stream_triad", "stream_mix32", "mfma_probe", "launch_count", "get_option", "set_option", "lib", "version", "LIB_PATH",
     "OPT_UPDATE_BLOCKS_PER_CU", "OPT_UPDATE_NONTEMPORAL", "OPT_UPDATE_GROUPS", "OPT_GEMM_TILE", "OPT_ROUND_OVERLAP", "OPT_GEMM_XCD", "OPT_GEMM_PAIR", "OPT_MLP_HEAD", "OPT_UPDATE_LAYOUT", "OPT_ROUND_SINGLE_LAUNCH", "OPT_ROUND_SPIN_LIMIT", "round_barrier_timeouts",
 )
 __all__ = list(_BINDING_NAMES) + ["BatchFeeder"]

@@ -86,6 +86,8 @@ def _load() -> ctypes.CDLL:
     lib.easgd_stream_triad.restype = i
     lib.easgd_stream_mix32.argtypes = [vp, vp, vp, vp, vp, sz, f, vp]
     lib.easgd_stream_mix32.restype = i
+    lib.easgd_mfma_probe.argtypes = [vp, sz, i, i, i, ctypes.POINTER(ctypes.c_uint), vp]
+    lib.easgd_mfma_probe.restype = i
     lib.easgd_round_barrier_timeouts.argtypes = [vp]
     lib.easgd_round_barrier_timeouts.restype = ctypes.c_long
     lib.easgd_launch_count.argtypes = []
@@ -385,6 +387,14 @@ def stream_mix32(a, b, c, d, e, s: float, stream=None) -> None:
     _check(_lib.easgd_stream_mix32(_dev("a", a, torch.float32, n), _dev("b", b, torch.float32, n),
                                    _dev("c", c, torch.float32, n), _dev("d", d, torch.float32, n),
                                    _dev("e", e, torch.float32, n), n, s, _stream(stream)))
+
+
+def mfma_probe(out, iters: int, lds_fetch: bool, blocks_per_cu: int = 2, stream=None) -> int:
+    """Measurement aid: the bare fp32 matrix-instruction loop (see include/easgd.h).  Returns the flops of the launch."""
+    blocks = ctypes.c_uint(0)
+    _check(_lib.easgd_mfma_probe(_dev("out", out, torch.float32, out.numel()), out.numel(), int(iters), 1 if lds_fetch else 0,
+                                 int(blocks_per_cu), ctypes.byref(blocks), _stream(stream)))
+    return blocks.value * 4 * int(iters) * 16 * 4096
 
 
 def round_barrier_timeouts(stream=None) -> int:

@@ -1,6 +1,7 @@
 // Measurement aids: plain streaming kernels of known traffic.  They are used to
 // measure this GPU's attainable HBM bandwidth (the ceiling the elastic update is
-// compared with) and to calibrate hardware byte counters.  Not part of the method.
+// compared with) and to calibrate hardware byte counters; and a bare matrix-core loop of
+// known flops, the ceiling the gradient's products are compared with.  Not part of the method.
 #include "common.h"
 
 namespace easgd {
@@ -98,6 +99,61 @@ static int probe_grid(size_t n4, dim3 &grid)
     return 0;
 }
 
+// The matrix-core yardstick: blocks of four wavefronts that do nothing but the inner loop of the 64x64x32 products,
+// v_mfma_f32_32x32x2_f32 on one accumulator tile per wavefront, over one 32-deep slab of operands that sits in LDS
+// (A[k][m] = probe_value(64k + m), B[k][n] = probe_value(1000 + 64k + n), pitch 64 + 4 as in the products).
+// LDS_FETCH = false: every lane reads its 16 + 16 operand values once and multiplies from registers: the matrix
+// cores alone.  LDS_FETCH = true: the operands are fetched from LDS again for every pass over the slab, two
+// ds_read_b32 per MFMA as in the products: matrix cores plus their feeding, still without global memory, barriers
+// or epilogues.  Each pass adds A^T B to the accumulators; out gets the 16 accumulator values of every lane.
+__device__ __forceinline__ float probe_value(int i) { return (float)((i * 37 + 11) % 64 - 32) * 0.03125f; }
+
+template <bool LDS_FETCH>
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out, int iters)
+{
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    constexpr int PITCH = 68;
+    __shared__ float lds[2 * 32 * PITCH];
+    for (int i = threadIdx.x; i < 2 * 32 * 64; i += 256) {
+        const int op = i / 2048, k = (i % 2048) / 64, x = i % 64;
+        lds[(op * 32 + k) * PITCH + x] = probe_value(op * 1000 + k * 64 + x);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // lane l supplies A[k = 2*step + l/32][m = l%32] and B[k][n = l%32] of its wavefront's 32x32 tile
+    const float *la = lds + (lane >> 5) * PITCH + (wave >> 1) * 32 + (lane & 31);
+    const float *lb = lds + (32 + (lane >> 5)) * PITCH + (wave & 1) * 32 + (lane & 31);
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    float ra[16], rb[16];
+#pragma unroll
+    for (int st = 0; st < 16; ++st) {
+        ra[st] = la[2 * st * PITCH];
+        rb[st] = lb[2 * st * PITCH];
+    }
+    float a = ra[0], b = rb[0];
+    for (int it = 0; it < iters; ++it) {
+        if constexpr (LDS_FETCH) asm volatile("" ::: "memory");      // the slab is read again on every pass
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            const int nx = (st + 1) & 15;
+            float an = ra[nx], bn = rb[nx];
+            if constexpr (LDS_FETCH) {       // the next step's operands are requested before this step's MFMA, as in the products
+                an = la[2 * nx * PITCH];
+                bn = lb[2 * nx * PITCH];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+            a = an;
+            b = bn;
+        }
+    }
+    float *o = out + ((size_t)blockIdx.x * 256 + threadIdx.x) * 16;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[r] = acc[r];
+}
+
 }  // namespace easgd
 
 extern "C" {
@@ -138,6 +194,24 @@ int easgd_stream_mix32(float *a, float *b, const float *c, const float *d, const
     EASGD_LAUNCH(stream_mix32_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), (f32x4 *)a, (f32x4 *)b,
                  (const f32x4 *)c, (const f32x4 *)d, (const f32x4 *)e, s, n / 4);
     return check_launch("easgd_stream_mix32");
+}
+
+int easgd_mfma_probe(float *out, size_t out_len, int iters, int lds_fetch, int blocks_per_cu, unsigned *blocks, void *stream)
+{
+    using namespace easgd;
+    if (!out || !aligned_to(out, 4)) return fail(EASGD_EINVAL, "easgd_mfma_probe: out must be a non-NULL fp32 pointer");
+    if (iters < 1 || iters > (1 << 20)) return fail(EASGD_EINVAL, "easgd_mfma_probe: iters must be in [1, 2^20], got %d", iters);
+    if (blocks_per_cu < 1 || blocks_per_cu > 8)
+        return fail(EASGD_EINVAL, "easgd_mfma_probe: blocks_per_cu must be in [1, 8], got %d", blocks_per_cu);
+    const unsigned n = (unsigned)blocks_per_cu * (unsigned)num_cus();
+    if (out_len < (size_t)n * 4096)
+        return fail(EASGD_EINVAL, "easgd_mfma_probe: out holds %zu floats, %zu needed", out_len, (size_t)n * 4096);
+    clear_error();
+    if (blocks) *blocks = n;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lds_fetch) EASGD_LAUNCH(mfma_probe_kernel<true>, dim3(n), dim3(256), 0, s, out, iters);
+    else EASGD_LAUNCH(mfma_probe_kernel<false>, dim3(n), dim3(256), 0, s, out, iters);
+    return check_launch("easgd_mfma_probe");
 }
 
 }  // extern "C"

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
             "easgd_get_option", "easgd_stream_copy", "easgd_stream_triad", "easgd_mlp_round", "easgd_mlp_round_bf16v",
             "easgd_mlp_round_workspace_bytes", "easgd_sync_round_bf16", "measgd_round_bf16", "measgd_round_bf16v",
             "easgd_grad_bf16", "easgd_grad_static", "sync_sgd_round", "easgd_stream_mix32",
-            "easgd_launch_count", "easgd_layer_product"} <= set(names)
+            "easgd_launch_count", "easgd_layer_product", "easgd_mfma_probe"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/easgd.h but not exported"
 

@@ -340,23 +340,23 @@ def triad_ceiling(hip, n=488_000_000, reps=20):
 # them are dropped from the JSON line (traffic: null) when the running library reports another version than the one
 # that was profiled, or non-default launch options.
 TRAFFIC_PROFILES = {
-    ("elastic", False, 8, 61_000_000): (2_025_433.1 * 1024 * 2.000 + 2_144_531.4 * 1024 * 1.000,
+    ("elastic", False, 8, 61_000_000): (2_025_433.0 * 1024 * 2.000 + 2_144_531.4 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("elastic", True, 16, 61_000_000): (5_837_958.0 * 1024 * 2.000 + 7_863_311.1 * 1024 * 1.000,
+    ("elastic", True, 16, 61_000_000): (5_837_957.7 * 1024 * 2.000 + 7_863_297.3 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
     ("sync_sgd", False, 8, 61_000_000): (1_906_280.9 * 1024 * 2.000 + 1_906_252.9 * 1024 * 1.000,
                                          "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("async", False, 8, 61_000_000): (2_025_431.4 * 1024 * 2.000 + 2_144_531.2 * 1024 * 1.000,
+    ("async", False, 8, 61_000_000): (2_025_431.5 * 1024 * 2.000 + 2_144_531.3 * 1024 * 1.000,
                                       "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("hogwild", False, 8, 61_000_000): (2_869_617.3 * 1024 * 2.000 + 9_531_250.0 * 1024 * 1.000,
+    ("hogwild", False, 8, 61_000_000): (2_869_271.3 * 1024 * 2.000 + 9_531_250.0 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("elastic_bf16", False, 8, 61_000_000): (1_548_869.4 * 1024 * 2.000 + 2_144_531.8 * 1024 * 1.000,
+    ("elastic_bf16", False, 8, 61_000_000): (1_548_869.4 * 1024 * 2.000 + 2_144_531.9 * 1024 * 1.000,
                                              "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
     ("elastic_bf16", True, 16, 61_000_000): (3_931_723.9 * 1024 * 2.000 + 5_957_033.6 * 1024 * 1.000,
                                              "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("grad", "cfg2"): (131_055.7 * 1024 * 2.000 + 149_337.0 * 1024 * 1.000, "profiles/easgd_grad_cfg2_hbm_traffic.md"),
+    ("grad", "cfg2"): (131_058.3 * 1024 * 2.000 + 149_337.0 * 1024 * 1.000, "profiles/easgd_grad_cfg2_hbm_traffic.md"),
 }
-TRAFFIC_PROFILED_VERSION = 480      # easgd_version() of the library the summaries above were taken with
+TRAFFIC_PROFILED_VERSION = 490      # easgd_version() of the library the summaries above were taken with
 
 
 def traffic_fields(hip, key):

@@ -187,30 +187,45 @@ def bench_training(hip, wl, steps, warmup, one_call=True, v_bf16=False, g_bf16=F
             "launches_per_round": launches, "event_rounds": n_ev, **pre}
 
 
-def bench_host_fed(hip, wl, steps, warmup):
+def bench_host_fed(hip, wl, steps, warmup, group=1):
     """Whole rounds whose minibatches come from pinned host memory: the copy of round t+1 overlaps round t
-    (the overlap of Sync EASGD3, Algorithm 3), two device buffers."""
+    (the overlap of Sync EASGD3, Algorithm 3), two device buffers.  group = g > 1: one copy brings the minibatches
+    of g rounds and overlaps the g rounds before them."""
     import torch
+    steps, warmup = (steps + group - 1) // group * group, (warmup + group - 1) // group * group
     ld = workloads.round_up(wl.N, TRAINING_LD_ALIGN)
     w0 = workloads.init_packed_weights(wl)
     dW = torch.from_numpy(workloads.replicate(w0, wl.P, ld)).cuda()
     dWc = torch.from_numpy(w0.copy()).cuda()
     dV = torch.zeros_like(dW) if wl.momentum else None
     n_batches = min(wl.rounds, 16)
+    n_batches = (n_batches + group - 1) // group * group
+    new_feeder = lambda: hip.BatchFeeder(wl.P, wl.batch, wl.dims[0], rounds_per_copy=group)
     host = []
-    for t in range(n_batches):
-        X, y = workloads.minibatch(wl, t)
-        host.append((torch.from_numpy(X).pin_memory(), torch.from_numpy(y).pin_memory()))
-    bytes_per_round = host[0][0].numel() * 4 + host[0][1].numel() * 4
+    layout = new_feeder()                # its host_batch(): samples and labels back to back, one copy
+    for t0 in range(0, n_batches, group):
+        hX, hy = layout.host_batch()
+        for i in range(group):
+            X, y = workloads.minibatch(wl, t0 + i)
+            (hX[i] if group > 1 else hX).copy_(torch.from_numpy(X)); (hy[i] if group > 1 else hy).copy_(torch.from_numpy(y))
+        host.append((hX, hy))
+    del layout
+    bytes_per_round = (host[0][0].numel() * 4 + host[0][1].numel() * 4) // group
     ws = torch.empty(hip.easgd_mlp_round_workspace_bytes(wl.dims, wl.P, wl.batch), dtype=torch.uint8, device="cuda")
-    def run(feeder, first, count):
-        feeder.submit(first % 2, *host[first % n_batches])
-        for t in range(first, first + count):
-            if t + 1 < first + count:
-                feeder.submit((t + 1) % 2, *host[(t + 1) % n_batches])
-            X, y = feeder.acquire(t % 2)
-            hip.easgd_mlp_round(wl.dims, dW, dWc, X, y, wl.eta, wl.rho, V=dV, delta=wl.delta or 0.0, workspace=ws)
-            feeder.release(t % 2)
+    def run(feeder, first, count, primed=False):       # first and count are multiples of group
+        # leaves the copy for the round after its last one in flight, so that a run that continues where this one
+        # ended (primed=True) starts with a full pipeline: the timed region then holds no start-up copy that
+        # nothing overlaps
+        k0, kn = first // group, count // group
+        if not primed:
+            feeder.submit(k0 % 2, *host[k0 % len(host)])
+        for k in range(k0, k0 + kn):
+            feeder.submit((k + 1) % 2, *host[(k + 1) % len(host)])
+            X, y = feeder.acquire(k % 2)
+            for i in range(group):
+                hip.easgd_mlp_round(wl.dims, dW, dWc, X[i] if group > 1 else X, y[i] if group > 1 else y, wl.eta, wl.rho,
+                                    V=dV, delta=wl.delta or 0.0, workspace=ws)
+            feeder.release(k % 2)
 
     # Measured on this device: the copy overlaps the round only when the round runs on a stream of its own
     # (not the default stream) and the library keeps to that one stream (the center rule on extra blocks of a
@@ -224,7 +239,7 @@ def bench_host_fed(hip, wl, steps, warmup):
         best, done = None, 0
         # the host link and its copy engines take a while to reach their rate after start-up: the first fed
         # loop of a process runs 25 % slower than any later one, so about a second of untimed fed rounds goes first
-        feeder, cand = hip.BatchFeeder(wl.P, wl.batch, wl.dims[0]), torch.cuda.Stream()
+        feeder, cand = new_feeder(), torch.cuda.Stream()
         with torch.cuda.stream(cand):
             t_warm = time.perf_counter()
             while time.perf_counter() - t_warm < 1.0:
@@ -232,22 +247,22 @@ def bench_host_fed(hip, wl, steps, warmup):
                 torch.cuda.synchronize()
                 done += 100
         for _ in range(6):
-            feeder, cand = hip.BatchFeeder(wl.P, wl.batch, wl.dims[0]), torch.cuda.Stream()
+            feeder, cand = new_feeder(), torch.cuda.Stream()
             with torch.cuda.stream(cand):
                 run(feeder, done, warmup)
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
-                run(feeder, done + warmup, 30)
+                run(feeder, done + warmup, 32, primed=True)
                 torch.cuda.synchronize()
                 dt = time.perf_counter() - t0
-            done += warmup + 30
+            done += warmup + 32
             if best is None or dt < best[0]:
                 best = (dt, feeder, cand)
         with torch.cuda.stream(best[2]):
             run(best[1], done, warmup)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            run(best[1], done + warmup, steps)
+            run(best[1], done + warmup, steps, primed=True)
             torch.cuda.synchronize()
             elapsed = time.perf_counter() - t0
     finally:
@@ -256,8 +271,9 @@ def bench_host_fed(hip, wl, steps, warmup):
     return {"rounds_per_s": round(steps / elapsed, 2), "ms_per_step": round(1e3 * elapsed / steps, 4),
             "host_bytes_per_round": bytes_per_round,
             "host_GBs": round(bytes_per_round * steps / elapsed / 1e9, 2),
-            "note": "minibatches copied from pinned host memory each round, the copy of round t+1 overlapping "
-                    "round t; rounds on a non-default stream, library on one stream"}
+            "rounds_per_copy": group, "steps": steps,
+            "note": "minibatches copied from pinned host memory, the copy of the next round(s) overlapping the "
+                    "current one(s); rounds on a non-default stream, library on one stream"}
 
 
 def bench_update_only(hip, wl, steps, warmup, pool=3, rule="elastic"):
@@ -733,6 +749,9 @@ def main():
         # on the caller's queue, and the center rule no longer runs beside forward propagation (cfg3: 2.6 ms per
         # round instead of 2.4 ms when this leg ran first)
         line["host_fed"] = bench_host_fed(hip, wl, steps, warmup)
+        # the same with one copy per four rounds: a wait and a release between two streams cost the rounds' stream
+        # about 13 us a pair whatever the copy's size, which is 6 % of a cfg2 round
+        line["host_fed"]["four_rounds_per_copy"] = bench_host_fed(hip, wl, steps, warmup, group=4)
 
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, budget_s=8.0 if wl.has_grad else 4.0)

@@ -428,7 +428,7 @@ int easgd_stream_mix32(float *a, float *b, const float *c, const float *d, const
  * accumulator tile, as in the 64x64x32 tiles of easgd_grad.  lds_fetch = 0: operands stay in registers (the
  * matrix cores alone); lds_fetch = 1: every instruction's operands are fetched from LDS again (matrix cores
  * plus their feeding).  Flops per launch: blocks x 4 x iters x 16 x 4096.
- *   out     DEVICE out  [blocks x 256 x 16]  accumulator values (every pass adds the same 64x64 product, so
+ *   out     DEVICE out  [blocks][16][256]  accumulator register r of thread t of a block at [r][t] (every pass adds the same 64x64 product, so
  *                       out = iters x that product: lets a test check that the flops were really done)
  *   out_len elements available at out;  blocks  HOST out, may be NULL: the number of blocks launched
  *   iters in [1, 2^20], blocks_per_cu in [1, 8].  Errors: EASGD_EINVAL, EASGD_ELAUNCH.

@@ -105,7 +105,8 @@ static int probe_grid(size_t n4, dim3 &grid)
 // LDS_FETCH = false: every lane reads its 16 + 16 operand values once and multiplies from registers: the matrix
 // cores alone.  LDS_FETCH = true: the operands are fetched from LDS again for every pass over the slab, two
 // ds_read_b32 per MFMA as in the products: matrix cores plus their feeding, still without global memory, barriers
-// or epilogues.  Each pass adds A^T B to the accumulators; out gets the 16 accumulator values of every lane.
+// or epilogues.  Each pass adds A^T B to the accumulators; out gets the 16 accumulator values of every lane
+// (out[block][register][thread]).
 __device__ __forceinline__ float probe_value(int i) { return (float)((i * 37 + 11) % 64 - 32) * 0.03125f; }
 
 template <bool LDS_FETCH>
@@ -149,9 +150,9 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out
             b = bn;
         }
     }
-    float *o = out + ((size_t)blockIdx.x * 256 + threadIdx.x) * 16;
+    float *o = out + (size_t)blockIdx.x * 4096 + threadIdx.x;     // [block][register][thread]: coalesced stores
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[r] = acc[r];
+    for (int r = 0; r < 16; ++r) o[r * 256] = acc[r];
 }
 
 }  // namespace easgd

@@ -50,8 +50,8 @@ def test_mfma_probe_does_the_flops_it_claims(lds_fetch):
             expect[t, r] = C[(wave >> 1) * 32 + 8 * (r // 4) + 4 * (lane // 32) + r % 4, (wave & 1) * 32 + lane % 32]
     got = out.cpu().numpy()
     assert np.isnan(got[per_cu * cus * 4096:]).all()
-    got = got[:per_cu * cus * 4096].reshape(-1, 256, 16)
+    got = got[:per_cu * cus * 4096].reshape(-1, 16, 256)            # [block][register][thread]
     for b in (0, 1, got.shape[0] // 2, got.shape[0] - 1):
-        np.testing.assert_array_equal(got[b].astype(np.float64), expect)
+        np.testing.assert_array_equal(got[b].T.astype(np.float64), expect)
     with pytest.raises(hip.EasgdError):
         hip.mfma_probe(out[:100], iters, lds_fetch, per_cu)

@@ -356,23 +356,23 @@ def triad_ceiling(hip, n=488_000_000, reps=20):
 # them are dropped from the JSON line (traffic: null) when the running library reports another version than the one
 # that was profiled, or non-default launch options.
 TRAFFIC_PROFILES = {
-    ("elastic", False, 8, 61_000_000): (2_025_433.0 * 1024 * 2.000 + 2_144_531.4 * 1024 * 1.000,
+    ("elastic", False, 8, 61_000_000): (2_025_433.1 * 1024 * 2.000 + 2_144_531.5 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("elastic", True, 16, 61_000_000): (5_837_957.7 * 1024 * 2.000 + 7_863_297.3 * 1024 * 1.000,
+    ("elastic", True, 16, 61_000_000): (5_837_957.8 * 1024 * 2.000 + 7_863_310.1 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("sync_sgd", False, 8, 61_000_000): (1_906_280.9 * 1024 * 2.000 + 1_906_252.9 * 1024 * 1.000,
+    ("sync_sgd", False, 8, 61_000_000): (1_906_280.9 * 1024 * 2.000 + 1_906_253.1 * 1024 * 1.000,
                                          "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("async", False, 8, 61_000_000): (2_025_431.5 * 1024 * 2.000 + 2_144_531.3 * 1024 * 1.000,
+    ("async", False, 8, 61_000_000): (2_025_431.3 * 1024 * 2.000 + 2_144_531.3 * 1024 * 1.000,
                                       "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("hogwild", False, 8, 61_000_000): (2_869_271.3 * 1024 * 2.000 + 9_531_250.0 * 1024 * 1.000,
+    ("hogwild", False, 8, 61_000_000): (2_868_972.1 * 1024 * 2.000 + 9_531_250.0 * 1024 * 1.000,
                                         "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("elastic_bf16", False, 8, 61_000_000): (1_548_869.4 * 1024 * 2.000 + 2_144_531.9 * 1024 * 1.000,
+    ("elastic_bf16", False, 8, 61_000_000): (1_548_869.4 * 1024 * 2.000 + 2_144_531.7 * 1024 * 1.000,
                                              "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("elastic_bf16", True, 16, 61_000_000): (3_931_723.9 * 1024 * 2.000 + 5_957_033.6 * 1024 * 1.000,
+    ("elastic_bf16", True, 16, 61_000_000): (3_931_724.0 * 1024 * 2.000 + 5_957_033.4 * 1024 * 1.000,
                                              "profiles/elastic_update_cfg4_cfg5_hbm_traffic.md"),
-    ("grad", "cfg2"): (131_058.3 * 1024 * 2.000 + 149_337.0 * 1024 * 1.000, "profiles/easgd_grad_cfg2_hbm_traffic.md"),
+    ("grad", "cfg2"): (131_056.1 * 1024 * 2.000 + 149_337.0 * 1024 * 1.000, "profiles/easgd_grad_cfg2_hbm_traffic.md"),
 }
-TRAFFIC_PROFILED_VERSION = 490      # easgd_version() of the library the summaries above were taken with
+TRAFFIC_PROFILED_VERSION = 500      # easgd_version() of the library the summaries above were taken with
 
 
 def traffic_fields(hip, key):
@@ -504,24 +504,25 @@ def mfma_ceilings(hip, iters=2000, reps=5):
     import torch
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     out = torch.empty(2 * cus * 4096, dtype=torch.float32, device="cuda")
+    src = torch.randn(16 * 1024 * 1024, dtype=torch.float32, device="cuda")      # 64 MB: beyond the L2s, inside the last-level cache
     res = {}
-    for name, fetch in (("registers", False), ("lds_fetch", True)):
+    for name, fetch in (("registers", 0), ("lds_fetch", 1), ("lds_fetch_global_feed", 2)):
         for _ in range(5):                  # untimed: the clocks start slow
-            flops = hip.mfma_probe(out, iters, fetch, 2)
+            flops = hip.mfma_probe(out, iters, fetch, 2, src=src)
         e0, e1 = _events(1)[0], _events(1)[0]
         e0.record()
         for _ in range(reps):
-            hip.mfma_probe(out, iters, fetch, 2)
+            hip.mfma_probe(out, iters, fetch, 2, src=src)
         e1.record()
         torch.cuda.synchronize()
         res[name] = flops * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
     # the same loop in launches as short as a cfg2 forward product (25 passes = K 800), back to back on one stream:
     # what a kernel that did nothing but its matrix instructions would reach once launch boundaries are paid
-    flops = hip.mfma_probe(out, 25, True, 2)
+    flops = hip.mfma_probe(out, 25, 1, 2)
     e0, e1 = _events(1)[0], _events(1)[0]
     e0.record()
     for _ in range(200):
-        hip.mfma_probe(out, 25, True, 2)
+        hip.mfma_probe(out, 25, 1, 2)
     e1.record()
     torch.cuda.synchronize()
     res["short_launch"] = flops * 200 / (e0.elapsed_time(e1) * 1e-3) / 1e12
@@ -538,6 +539,7 @@ def mfma_roofline(hip, kernel, traffic_key, flops, ms):
         out["measured_mfma_loop_TFLOPs"] = round(MFMA_CEILINGS["registers"], 1)
         out["measured_mfma_loop_with_lds_fetch_TFLOPs"] = round(MFMA_CEILINGS["lds_fetch"], 1)
         out["frac_of_mfma_loop_with_lds_fetch"] = round(tflops / MFMA_CEILINGS["lds_fetch"], 4)
+        out["measured_mfma_loop_with_lds_fetch_and_global_feed_TFLOPs"] = round(MFMA_CEILINGS["lds_fetch_global_feed"], 1)
         out["measured_mfma_loop_in_short_launches"] = {
             "TFLOPs": round(MFMA_CEILINGS["short_launch"], 1), "us_per_launch": round(MFMA_CEILINGS["short_launch_us"], 2),
             "note": "the LDS-fetch loop in back-to-back launches of 25 passes (3.36 GFLOP, the size of cfg2's first "

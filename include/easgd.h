@@ -422,18 +422,24 @@ int easgd_stream_triad(float *a, const float *b, const float *c, size_t n, float
 int easgd_stream_mix32(float *a, float *b, const float *c, const float *d, const float *e, size_t n, float s, void *stream);
 
 /*
- * Measurement aid: the attainable rate of the fp32 matrix instruction the products use (32x32x2), without global
- * memory, barriers or epilogues.  blocks_per_cu x (compute units) blocks of four wavefronts each run `iters`
- * passes over one 32-deep slab of operands held in LDS; a pass is 16 matrix instructions per wavefront on one
- * accumulator tile, as in the 64x64x32 tiles of easgd_grad.  lds_fetch = 0: operands stay in registers (the
- * matrix cores alone); lds_fetch = 1: every instruction's operands are fetched from LDS again (matrix cores
- * plus their feeding).  Flops per launch: blocks x 4 x iters x 16 x 4096.
- *   out     DEVICE out  [blocks][16][256]  accumulator register r of thread t of a block at [r][t] (every pass adds the same 64x64 product, so
- *                       out = iters x that product: lets a test check that the flops were really done)
+ * Measurement aid: the attainable rate of the fp32 matrix instruction the products use (32x32x2), without the
+ * products' epilogues.  blocks_per_cu x (compute units) blocks of four wavefronts each run `iters` passes over one
+ * 32-deep slab of operands held in LDS; a pass is 16 matrix instructions per wavefront on one accumulator tile, as
+ * in the 64x64x32 tiles of easgd_grad.  mode 0: operands stay in registers (the matrix cores alone); mode 1: every
+ * instruction's operands are fetched from LDS again (matrix cores plus their feeding); mode 2: as 1, and every pass
+ * also requests 16 KB from global memory one pass ahead, stores it to LDS and ends in a barrier, which is what a
+ * slab of the products' K loop does besides its matrix instructions (the loaded values are not multiplied).
+ * Flops per launch: blocks x 4 x iters x 16 x 4096.
+ *   out     DEVICE out  [blocks][16][256]  accumulator register r of thread t of a block at [r][t] (every pass adds
+ *                       the same 64x64 product, so out = iters x that product in every mode: lets a test check that
+ *                       the flops were really done)
  *   out_len elements available at out;  blocks  HOST out, may be NULL: the number of blocks launched
+ *   src     DEVICE in   [src_len] floats, 16-byte aligned, src_len >= 4096: what mode 2 reads, in pieces of 4096
+ *                       floats, block x piece (977 x + pass) mod (src_len / 4096); ignored (may be NULL) otherwise
  *   iters in [1, 2^20], blocks_per_cu in [1, 8].  Errors: EASGD_EINVAL, EASGD_ELAUNCH.
  */
-int easgd_mfma_probe(float *out, size_t out_len, int iters, int lds_fetch, int blocks_per_cu, unsigned *blocks, void *stream);
+int easgd_mfma_probe(float *out, size_t out_len, int iters, int mode, int blocks_per_cu, const float *src, size_t src_len,
+                     unsigned *blocks, void *stream);
 
 /* Number of blocks that ever gave up waiting at the barrier of a single-launch round on `stream` of the
  * current device (0 unless something kept part of a grid from running for seconds).  Synchronises `stream`.

@@ -86,7 +86,7 @@ def _load() -> ctypes.CDLL:
     lib.easgd_stream_triad.restype = i
     lib.easgd_stream_mix32.argtypes = [vp, vp, vp, vp, vp, sz, f, vp]
     lib.easgd_stream_mix32.restype = i
-    lib.easgd_mfma_probe.argtypes = [vp, sz, i, i, i, ctypes.POINTER(ctypes.c_uint), vp]
+    lib.easgd_mfma_probe.argtypes = [vp, sz, i, i, i, vp, sz, ctypes.POINTER(ctypes.c_uint), vp]
     lib.easgd_mfma_probe.restype = i
     lib.easgd_round_barrier_timeouts.argtypes = [vp]
     lib.easgd_round_barrier_timeouts.restype = ctypes.c_long
@@ -389,11 +389,14 @@ def stream_mix32(a, b, c, d, e, s: float, stream=None) -> None:
                                    _dev("e", e, torch.float32, n), n, s, _stream(stream)))
 
 
-def mfma_probe(out, iters: int, lds_fetch: bool, blocks_per_cu: int = 2, stream=None) -> int:
-    """Measurement aid: the bare fp32 matrix-instruction loop (see include/easgd.h).  Returns the flops of the launch."""
+def mfma_probe(out, iters: int, mode, blocks_per_cu: int = 2, src=None, stream=None) -> int:
+    """Measurement aid: the bare fp32 matrix-instruction loop (see include/easgd.h; mode 0, 1 or 2, a bool counts as
+    0 or 1; mode 2 reads `src`).  Returns the flops of the launch."""
     blocks = ctypes.c_uint(0)
-    _check(_lib.easgd_mfma_probe(_dev("out", out, torch.float32, out.numel()), out.numel(), int(iters), 1 if lds_fetch else 0,
-                                 int(blocks_per_cu), ctypes.byref(blocks), _stream(stream)))
+    mode = int(mode)
+    src_ptr, src_len = (None, 0) if src is None else (_dev("src", src, torch.float32, 4096), src.numel())
+    _check(_lib.easgd_mfma_probe(_dev("out", out, torch.float32, out.numel()), out.numel(), int(iters), mode,
+                                 int(blocks_per_cu), src_ptr, src_len, ctypes.byref(blocks), _stream(stream)))
     return blocks.value * 4 * int(iters) * 16 * 4096
 
 

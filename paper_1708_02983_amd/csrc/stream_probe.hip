@@ -109,12 +109,19 @@ static int probe_grid(size_t n4, dim3 &grid)
 // (out[block][register][thread]).
 __device__ __forceinline__ float probe_value(int i) { return (float)((i * 37 + 11) % 64 - 32) * 0.03125f; }
 
-template <bool LDS_FETCH>
-__global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out, int iters)
+// MODE 0: operands in registers; 1: fetched from LDS; 2: as 1, and every pass also does what a slab of the products'
+// K loop does besides its MFMAs: 16 KB of operands requested from global memory one pass ahead (four 128-bit loads
+// per thread, a different 16 KB piece of `src` every pass), stored to LDS, one barrier.  The loaded values go to an
+// LDS region of their own and do not enter the products, so out is the same in all modes.
+template <int MODE>
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out, int iters,
+                                                         const f32x4 *__restrict__ src, unsigned src_pieces)
 {
     typedef float f32x16 __attribute__((ext_vector_type(16)));
+    constexpr bool LDS_FETCH = MODE >= 1, FEED = MODE == 2;
     constexpr int PITCH = 68;
     __shared__ float lds[2 * 32 * PITCH];
+    __shared__ f32x4 staged[FEED ? 1024 : 1];
     for (int i = threadIdx.x; i < 2 * 32 * 64; i += 256) {
         const int op = i / 2048, k = (i % 2048) / 64, x = i % 64;
         lds[(op * 32 + k) * PITCH + x] = probe_value(op * 1000 + k * 64 + x);
@@ -133,9 +140,31 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out
         ra[st] = la[2 * st * PITCH];
         rb[st] = lb[2 * st * PITCH];
     }
+    // piece p of src is 1024 groups of four floats; block x reads pieces (977 x + pass) mod src_pieces, the next
+    // piece's number kept by scalar increments (no division in the loop)
+    unsigned p_next = (blockIdx.x * 977u) % src_pieces;
+    auto next_piece = [&]() {
+        const f32x4 *at = src + (size_t)p_next * 1024 + threadIdx.x;
+        p_next = (p_next + 1 == src_pieces) ? 0u : p_next + 1;
+        return at;
+    };
+    // Two register stages, as in the products: at the top of a pass the piece two passes ahead is requested into
+    // the stage that is free, half way through the pass the piece requested a pass and a half ago moves from the
+    // other stage to LDS, and the pass ends in a barrier.
+    f32x4 r0[4], r1[4];
+    if constexpr (FEED) {
+        const f32x4 *at = next_piece();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) r1[q] = at[q * 256];
+    }
     float a = ra[0], b = rb[0];
-    for (int it = 0; it < iters; ++it) {
+    auto pass = [&](f32x4 (&refill)[4], f32x4 (&arrived)[4]) {
         if constexpr (LDS_FETCH) asm volatile("" ::: "memory");      // the slab is read again on every pass
+        if constexpr (FEED) {
+            const f32x4 *at = next_piece();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) refill[q] = at[q * 256];
+        }
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
             const int nx = (st + 1) & 15;
@@ -148,8 +177,22 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
             a = an;
             b = bn;
+            if constexpr (FEED) {
+                if (st == 7) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) staged[q * 256 + threadIdx.x] = arrived[q];
+                }
+            }
         }
+        if constexpr (FEED) __syncthreads();
+    };
+    int it = 0;
+    for (; it + 1 < iters; it += 2) {
+        pass(r0, r1);
+        pass(r1, r0);
     }
+    if (it < iters) pass(r0, r1);
+    if constexpr (FEED) acc[0] += 0.f * staged[(threadIdx.x * 5) & 1023][0];      // keeps the staging alive; adds zero
     float *o = out + (size_t)blockIdx.x * 4096 + threadIdx.x;     // [block][register][thread]: coalesced stores
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[r * 256] = acc[r];
@@ -197,21 +240,28 @@ int easgd_stream_mix32(float *a, float *b, const float *c, const float *d, const
     return check_launch("easgd_stream_mix32");
 }
 
-int easgd_mfma_probe(float *out, size_t out_len, int iters, int lds_fetch, int blocks_per_cu, unsigned *blocks, void *stream)
+int easgd_mfma_probe(float *out, size_t out_len, int iters, int mode, int blocks_per_cu, const float *src, size_t src_len,
+                     unsigned *blocks, void *stream)
 {
     using namespace easgd;
     if (!out || !aligned_to(out, 4)) return fail(EASGD_EINVAL, "easgd_mfma_probe: out must be a non-NULL fp32 pointer");
     if (iters < 1 || iters > (1 << 20)) return fail(EASGD_EINVAL, "easgd_mfma_probe: iters must be in [1, 2^20], got %d", iters);
+    if (mode < 0 || mode > 2) return fail(EASGD_EINVAL, "easgd_mfma_probe: mode must be 0, 1 or 2, got %d", mode);
     if (blocks_per_cu < 1 || blocks_per_cu > 8)
         return fail(EASGD_EINVAL, "easgd_mfma_probe: blocks_per_cu must be in [1, 8], got %d", blocks_per_cu);
+    if (mode == 2 && (!src || !aligned16(src) || src_len < 4096 || src_len / 4096 > 0x7fffffffu))
+        return fail(EASGD_EINVAL, "easgd_mfma_probe: mode 2 needs a 16-byte aligned src of at least 4096 floats");
     const unsigned n = (unsigned)blocks_per_cu * (unsigned)num_cus();
     if (out_len < (size_t)n * 4096)
         return fail(EASGD_EINVAL, "easgd_mfma_probe: out holds %zu floats, %zu needed", out_len, (size_t)n * 4096);
     clear_error();
     if (blocks) *blocks = n;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (lds_fetch) EASGD_LAUNCH(mfma_probe_kernel<true>, dim3(n), dim3(256), 0, s, out, iters);
-    else EASGD_LAUNCH(mfma_probe_kernel<false>, dim3(n), dim3(256), 0, s, out, iters);
+    const f32x4 *src4 = reinterpret_cast<const f32x4 *>(src);
+    const unsigned pieces = mode == 2 ? (unsigned)(src_len / 4096) : 1u;
+    if (mode == 2) EASGD_LAUNCH(mfma_probe_kernel<2>, dim3(n), dim3(256), 0, s, out, iters, src4, pieces);
+    else if (mode == 1) EASGD_LAUNCH(mfma_probe_kernel<1>, dim3(n), dim3(256), 0, s, out, iters, src4, pieces);
+    else EASGD_LAUNCH(mfma_probe_kernel<0>, dim3(n), dim3(256), 0, s, out, iters, src4, pieces);
     return check_launch("easgd_mfma_probe");
 }
 

@@ -28,7 +28,7 @@ def test_probes(n):
     assert bool(torch.isnan(a[n:]).all()) and bool(torch.isnan(a2[n:]).all())
 
 
-@pytest.mark.parametrize("lds_fetch", [False, True], ids=["registers", "lds"])
+@pytest.mark.parametrize("lds_fetch", [0, 1, 2], ids=["registers", "lds", "lds+global_feed"])
 def test_mfma_probe_does_the_flops_it_claims(lds_fetch):
     """Every pass of the matrix-core yardstick adds the 64x64 product A^T B of its slab to the accumulators (values
     are multiples of 1/32, so a few passes are exact): out must hold iters x that product in every block, in the
@@ -37,7 +37,8 @@ def test_mfma_probe_does_the_flops_it_claims(lds_fetch):
     iters, per_cu = 3, 1
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     out = torch.full((per_cu * cus * 4096 + 5,), float("nan"), device="cuda")
-    flops = hip.mfma_probe(out, iters, lds_fetch, per_cu)
+    src = torch.randn(5 * 4096 + 100, device="cuda") if lds_fetch == 2 else None     # five pieces and a remainder
+    flops = hip.mfma_probe(out, iters, lds_fetch, per_cu, src=src)
     assert flops == per_cu * cus * 4 * iters * 16 * 4096
     val = lambda i: ((i * 37 + 11) % 64 - 32) / 32.0
     A = np.array([[val(k * 64 + m) for m in range(64)] for k in range(32)])
@@ -54,4 +55,6 @@ def test_mfma_probe_does_the_flops_it_claims(lds_fetch):
     for b in (0, 1, got.shape[0] // 2, got.shape[0] - 1):
         np.testing.assert_array_equal(got[b].T.astype(np.float64), expect)
     with pytest.raises(hip.EasgdError):
-        hip.mfma_probe(out[:100], iters, lds_fetch, per_cu)
+        hip.mfma_probe(out[:100], iters, lds_fetch, per_cu, src=src)
+    with pytest.raises(hip.EasgdError):
+        hip.mfma_probe(out, iters, 2, per_cu)                       # mode 2 without a source
